@@ -102,7 +102,9 @@ typedef struct {
 
 #define PHOTON_MAX_CLIENTS 64
 
-/* Squared L2 norms of the averaged pseudo-gradient and of each client's (AggMetrics). */
+/* Squared L2 norms of the averaged pseudo-gradient and of each client's pseudo-gradient
+ * Delta_k = theta - theta_k, taken against the model as it was before the server step
+ * (AggMetrics).  Entries k >= K are zero. */
 typedef struct {
     double delta_norm2;
     double client_norm2[PHOTON_MAX_CLIENTS];
@@ -154,7 +156,8 @@ int64_t photon_workspace_bytes(const photon_ctx *ctx);
  *   opt_state       HOST struct; m, v DEVICE float32[N].
  *   token_batches   DEVICE int32 [n_steps][n_micro][micro_batch][seq_len + 1], ids in [0, vocab);
  *                   inputs are [..., :seq_len], the target of position t is token t + 1.
- *                   Ids outside the range are not checked.
+ *                   An id outside the range returns PHOTON_EINVAL before any step runs (the
+ *                   ids are checked on the device; this costs one stream synchronisation).
  *   n_micro         micro-batches whose gradients are averaged into one optimizer step.
  *   lr_schedule     HOST float[n_steps]: the learning rate of each step (the caller evaluates the
  *                   cosine / warm-up schedule over sequential steps).
@@ -168,8 +171,8 @@ int photon_client_local_steps(photon_ctx *ctx, float *params, photon_opt_state *
 
 /*
  * Loss and gradient of ONE micro-batch, no update (the "compute loss / compute gradients" lines
- * of Alg. 3).  tokens: DEVICE int32 [micro_batch][seq_len + 1].  grads_out: DEVICE float32[N],
- * overwritten.  loss_out: HOST float[1].
+ * of Alg. 3).  tokens: DEVICE int32 [micro_batch][seq_len + 1], ids in [0, vocab) (checked,
+ * PHOTON_EINVAL otherwise).  grads_out: DEVICE float32[N], overwritten.  loss_out: HOST float[1].
  */
 int photon_client_loss_grad(photon_ctx *ctx, const float *params, const int32_t *tokens,
                             float *grads_out, float *loss_out);
@@ -197,7 +200,8 @@ int photon_export_delta(photon_ctx *ctx, const float *global_params, const float
  *   theta <- ServerOpt(theta, Delta)                     (see photon_outer_opt)
  *   global_params   DEVICE float32[N], updated in place.
  *   client_bufs     HOST array of K DEVICE pointers; contents per `kind` / `dtype`
- *                   (PARAMS requires dtype FP32).
+ *                   (PARAMS requires dtype FP32).  No client buffer may overlap global_params
+ *                   or outer_opt->momentum, nor those two each other (PHOTON_EINVAL).
  *   client_weights  HOST double[K]: unnormalised, finite, >= 0, sum > 0 (equal weights give the
  *                   1/|C| mean of Alg. 1; token counts give the weighted FedAvg).
  *   outer_opt       HOST struct, see above; round is incremented.

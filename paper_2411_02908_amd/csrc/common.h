@@ -160,17 +160,18 @@ __device__ __forceinline__ unsigned lds_addr(const void *p) {
 // copies).  The kernels wait for their copies themselves with s_waitcnt vmcnt(n) before the
 // barrier that publishes a tile; the waits that the compiler adds for its own loads and stores
 // can only be stricter than it thinks, never weaker, because the counter retires in order.
-// m0 holds the LDS address of the copy; nothing else in these kernels uses m0.
+// The LDS address of the copy travels in m0, bound as an input operand so that the compiler
+// writes the register itself and knows its value.
 __device__ __forceinline__ void copy16_to_lds(rsrc_t rsrc, unsigned lds_byte_addr, int voff, int soff) {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+    asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds"
                  :
-                 : "s"(lds_byte_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "v"(voff), "s"(rsrc), "s"(soff), "{m0}"(lds_byte_addr)
                  : "memory");
 }
 __device__ __forceinline__ void copy4_to_lds(rsrc_t rsrc, unsigned lds_byte_addr, int voff, int soff) {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+    asm volatile("buffer_load_dword %0, %1, %2 offen lds"
                  :
-                 : "s"(lds_byte_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "v"(voff), "s"(rsrc), "s"(soff), "{m0}"(lds_byte_addr)
                  : "memory");
 }
 

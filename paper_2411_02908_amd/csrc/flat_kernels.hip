@@ -180,7 +180,7 @@ __device__ __forceinline__ float outer_elem(float th, float delta, float &b, con
 }
 
 // KT > 0: exactly KT clients, register accumulators, per-client norms.  KT == 0: run-time K
-// (no per-client norms; they are taken by sumsq_kernel when asked for).
+// (no per-client norms; sumsq_kernel takes them beforehand when they are asked for).
 template <int KIND, int KT, bool MOM>
 __global__ __launch_bounds__(kThreads) void aggregate_kernel(float *__restrict__ theta, float *__restrict__ mom,
                                                               ClientArgs ca, int K, OuterScalars os, int64_t n,
@@ -283,18 +283,26 @@ __global__ __launch_bounds__(kThreads) void aggregate_kernel(float *__restrict__
     }
 }
 
-// Sum of squares of one vector into its row of slots.
-template <typename T>
-__global__ __launch_bounds__(kThreads) void sumsq_kernel(const T *__restrict__ x, int64_t n,
-                                                          float *__restrict__ partials) {
+// Sum of squares of one client's pseudo-gradient into its row of slots: the buffer itself
+// (KIND = deltas) or theta - buffer (KIND = client parameters).
+template <int KIND>
+__global__ __launch_bounds__(kThreads) void sumsq_kernel(const void *__restrict__ x, const float *__restrict__ theta,
+                                                          int64_t n, float *__restrict__ partials) {
     __shared__ float red[kThreads / PHOTON_WAVE];
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     double acc = 0.0;
     const int64_t nvec = n >> 3;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += stride) {
-        float d[8];
-        const float zero[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        load_delta8<sizeof(T) == 2 ? KIND_DELTA_BF16 : KIND_DELTA_F32>(x, i, zero, d);
+        float d[8], th[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if constexpr (KIND == KIND_PARAMS_F32) {
+            const f32x4 t0 = ldg4(theta + 8 * i), t1 = ldg4(theta + 8 * i + 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                th[j] = t0[j];
+                th[j + 4] = t1[j];
+            }
+        }
+        load_delta8<KIND>(x, i, th, d);
         float sq = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) sq = fmaf(d[j], d[j], sq);
@@ -303,7 +311,7 @@ __global__ __launch_bounds__(kThreads) void sumsq_kernel(const T *__restrict__ x
     if (blockIdx.x == 0) {
         const int64_t i = (nvec << 3) + threadIdx.x;
         if (i < n) {
-            const float d = to_f32(x[i]);
+            const float d = load_delta1<KIND>(x, i, KIND == KIND_PARAMS_F32 ? theta[i] : 0.f);
             acc += (double)(d * d);
         }
     }
@@ -430,63 +438,71 @@ int flat_export_delta(photon_ctx *ctx, const float *gl, const float *cl, void *o
     return PHOTON_OK;
 }
 
-int flat_aggregate(photon_ctx *ctx, float *global, const void *const *bufs, int K, int kind, int dtype,
-                   const float *wnorm, photon_outer_opt *oo, photon_agg_metrics *metrics, int64_t n) {
+// Kernel launches of one aggregation on `st`: the fused weighted sum + server step, and, when
+// norms_dev is given, the squared norms (averaged pseudo-gradient first, then the K clients')
+// as float64 in norms_dev[0 .. K].  `part` holds (K + 1) rows of kBlocks slots; every slot that is
+// read is written first by this call.  Nothing here allocates or synchronises.
+static void aggregate_launches(hipStream_t st, float *global, const void *const *bufs, int K, int kind, int dtype,
+                               const float *wnorm, const photon_outer_opt *oo, int64_t n, float *part,
+                               double *norms_dev) {
     ClientArgs ca{};
     for (int k = 0; k < K; ++k) {
         ca.ptr[k] = bufs[k];
         ca.w[k] = wnorm[k];
     }
-    OuterScalars os{oo->eta_s, oo->mu, oo->nesterov};
+    const OuterScalars os{oo->eta_s, oo->mu, oo->nesterov};
     const bool mom = oo->mu != 0.0f;
-    hipStream_t st = ctx->stream;
-    float *part = ctx->norm_partials;
+    const int kk = kind == PHOTON_CLIENT_PARAMS ? KIND_PARAMS_F32 : dtype == PHOTON_FP32 ? KIND_DELTA_F32 : KIND_DELTA_BF16;
+    if (norms_dev && K > 8) {
+        // the run-time-K kernel takes no per-client norms: one pass per client, before the global
+        // model moves (client parameters are turned into pseudo-gradients against the old model)
+        for (int k = 0; k < K; ++k) {
+            float *row = part + (int64_t)(k + 1) * kBlocks;
+            if (kk == KIND_PARAMS_F32)
+                hipLaunchKernelGGL((sumsq_kernel<KIND_PARAMS_F32>), dim3(kBlocks), dim3(kThreads), 0, st, bufs[k], global, n, row);
+            else if (kk == KIND_DELTA_F32)
+                hipLaunchKernelGGL((sumsq_kernel<KIND_DELTA_F32>), dim3(kBlocks), dim3(kThreads), 0, st, bufs[k], global, n, row);
+            else
+                hipLaunchKernelGGL((sumsq_kernel<KIND_DELTA_BF16>), dim3(kBlocks), dim3(kThreads), 0, st, bufs[k], global, n, row);
+        }
+    }
     {
-        const double client_b = (kind == PHOTON_CLIENT_DELTAS && dtype == PHOTON_BF16) ? 2.0 : 4.0;
+        const double client_b = kk == KIND_DELTA_BF16 ? 2.0 : 4.0;
         TimedLaunch tl(st, KC_AGG, (double)n * (client_b * K + 8.0 + (mom ? 8.0 : 0.0)));
-        if (kind == PHOTON_CLIENT_PARAMS)
+        if (kk == KIND_PARAMS_F32)
             dispatch_aggregate<KIND_PARAMS_F32>(mom, st, global, oo->momentum, ca, K, os, n, part);
-        else if (dtype == PHOTON_FP32)
+        else if (kk == KIND_DELTA_F32)
             dispatch_aggregate<KIND_DELTA_F32>(mom, st, global, oo->momentum, ca, K, os, n, part);
         else
             dispatch_aggregate<KIND_DELTA_BF16>(mom, st, global, oo->momentum, ca, K, os, n, part);
     }
+    if (norms_dev)
+        hipLaunchKernelGGL(finish_norms_kernel, dim3(K + 1), dim3(kThreads), 0, st, part, kBlocks, norms_dev);
+}
+
+int flat_aggregate(photon_ctx *ctx, float *global, const void *const *bufs, int K, int kind, int dtype,
+                   const float *wnorm, photon_outer_opt *oo, photon_agg_metrics *metrics, int64_t n) {
+    hipStream_t st = ctx->stream;
+    aggregate_launches(st, global, bufs, K, kind, dtype, wnorm, oo, n, ctx->norm_partials,
+                       metrics ? ctx->norm_out : nullptr);
     HIP_TRY(ctx, hipGetLastError());
     oo->round += 1;
     if (!metrics) return PHOTON_OK;
-
-    if (K > 8) {
-        // run-time-K kernel took no per-client norms: one pass per client.  For PARAMS the
-        // global model has already moved, so those norms are not available any more.
-        for (int k = 0; k < K; ++k) {
-            float *row = part + (int64_t)(k + 1) * kBlocks;
-            if (kind == PHOTON_CLIENT_PARAMS) {
-                fill_zero_f32(st, row, kBlocks);
-            } else if (dtype == PHOTON_BF16) {
-                hipLaunchKernelGGL((sumsq_kernel<bf16>), dim3(kBlocks), dim3(kThreads), 0, st, (const bf16 *)bufs[k], n, row);
-            } else {
-                hipLaunchKernelGGL((sumsq_kernel<float>), dim3(kBlocks), dim3(kThreads), 0, st, (const float *)bufs[k], n, row);
-            }
-        }
-    }
-    hipLaunchKernelGGL(finish_norms_kernel, dim3(K + 1), dim3(kThreads), 0, st, part, kBlocks, ctx->norm_out);
-    HIP_TRY(ctx, hipGetLastError());
     HIP_TRY(ctx, hipMemcpyAsync(ctx->norm_host, ctx->norm_out, sizeof(double) * (K + 1), hipMemcpyDeviceToHost, st));
     HIP_TRY(ctx, hipStreamSynchronize(st));
     metrics->delta_norm2 = ctx->norm_host[0];
     for (int k = 0; k < PHOTON_MAX_CLIENTS; ++k) metrics->client_norm2[k] = k < K ? ctx->norm_host[k + 1] : 0.0;
-    if (K > 8 && kind == PHOTON_CLIENT_PARAMS)
-        for (int k = 0; k < K; ++k) metrics->client_norm2[k] = -1.0;  // not available
     return PHOTON_OK;
 }
 
 int flat_clip(photon_ctx *ctx, void *delta, int dtype, double max_norm, double *norm_out, int64_t n) {
     hipStream_t st = ctx->stream;
+    const float *none = nullptr;
     if (dtype == PHOTON_BF16)
-        hipLaunchKernelGGL((sumsq_kernel<bf16>), dim3(kBlocks), dim3(kThreads), 0, st, (const bf16 *)delta, n,
+        hipLaunchKernelGGL((sumsq_kernel<KIND_DELTA_BF16>), dim3(kBlocks), dim3(kThreads), 0, st, (const void *)delta, none, n,
                            ctx->norm_partials);
     else
-        hipLaunchKernelGGL((sumsq_kernel<float>), dim3(kBlocks), dim3(kThreads), 0, st, (const float *)delta, n,
+        hipLaunchKernelGGL((sumsq_kernel<KIND_DELTA_F32>), dim3(kBlocks), dim3(kThreads), 0, st, (const void *)delta, none, n,
                            ctx->norm_partials);
     hipLaunchKernelGGL(finish_norms_kernel, dim3(1), dim3(kThreads), 0, st, ctx->norm_partials, kBlocks, ctx->norm_out);
     if (dtype == PHOTON_BF16)

@@ -127,9 +127,9 @@ struct OperandCopy {
 template <bool KS>
 __device__ __forceinline__ void load_tile_part(rsrc_t tile, const OperandCopy<KS> &oc, bf16 *lds_tile, int wave,
                                                int t) {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+    asm volatile("buffer_load_dwordx4 %0, %1, 0 offen lds"
                  :
-                 : "s"(lds_addr(lds_tile) + OperandCopy<KS>::kib(wave, t) * 1024), "v"(oc.v[t]), "s"(tile)
+                 : "v"(oc.v[t]), "s"(tile), "{m0}"(lds_addr(lds_tile) + OperandCopy<KS>::kib(wave, t) * 1024)
                  : "memory");
 }
 

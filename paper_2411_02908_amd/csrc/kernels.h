@@ -93,6 +93,9 @@ void cross_entropy_fwd_bwd(hipStream_t st, T *logits, int ldz, int V, const int3
 // acc[0] += scale * sum(loss_rows[0..M)) in a fixed order, float64.
 void loss_reduce(hipStream_t st, const float *loss_rows, int M, double scale, double *acc);
 
+// flag[0] (device) = 1 if any of the n ids lies outside [0, V), else 0.
+void token_range_check(hipStream_t st, const int32_t *tokens, int64_t n, int V, int *flag);
+
 void convert_f32_to_bf16(hipStream_t st, const float *src, bf16 *dst, int64_t n);
 // dst [cols, rows] = transpose of src [rows, cols]
 void transpose_bf16(hipStream_t st, const bf16 *src, bf16 *dst, int rows, int cols);

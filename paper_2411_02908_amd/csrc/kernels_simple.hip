@@ -629,6 +629,19 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16 *__restr
     }
 }
 
+// flag[0] = 1 if any id lies outside [0, V).  Every writer stores the same value, so plain
+// stores suffice.
+__global__ __launch_bounds__(256) void token_range_kernel(const int32_t *__restrict__ tok, int64_t n, int V,
+                                                           int *__restrict__ flag) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    bool bad = false;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        const int t = tok[i];
+        bad |= (t < 0) | (t >= V);
+    }
+    if (bad) flag[0] = 1;
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, int64_t n) {
     const int64_t nvec = n >> 2;
     const int64_t stride = (int64_t)gridDim.x * 256;
@@ -803,6 +816,13 @@ void convert_f32_to_bf16(hipStream_t st, const float *src, bf16 *dst, int64_t n)
 void transpose_bf16(hipStream_t st, const bf16 *src, bf16 *dst, int rows, int cols) {
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, st, src, dst, rows,
                        cols);
+}
+
+void token_range_check(hipStream_t st, const int32_t *tokens, int64_t n, int V, int *flag) {
+    fill_zero_f32(st, reinterpret_cast<float *>(flag), 1);
+    const int64_t want = (n + 255) / 256;
+    hipLaunchKernelGGL(token_range_kernel, dim3((unsigned)(want < 1024 ? (want > 0 ? want : 1) : 1024)), dim3(256), 0, st,
+                       tokens, n, V, flag);
 }
 
 void fill_zero_f32(hipStream_t st, float *p, int64_t n) {

@@ -60,6 +60,7 @@ struct ModelWorkspace {
     void *y = nullptr, *logits = nullptr;
     float *loss_rows = nullptr;
     double *loss_acc = nullptr;  // device, one per step
+    int *tok_flag = nullptr;     // device: set by the token-id range check
     int loss_cap = 0;
     // backward temporaries
     float *dx_a = nullptr, *dx_b = nullptr, *dvec = nullptr, *ln_scratch = nullptr;
@@ -286,6 +287,7 @@ int alloc_workspace(photon_ctx *ctx) {
     TRY_RC(dev_alloc(ctx, &w.loss_rows, sizeof(float) * (size_t)M));
     w.loss_cap = 4096;
     TRY_RC(dev_alloc(ctx, &w.loss_acc, sizeof(double) * (size_t)w.loss_cap));
+    TRY_RC(dev_alloc(ctx, &w.tok_flag, 16));
     TRY_RC(dev_alloc(ctx, &w.dx_a, sizeof(float) * (size_t)(M * d)));
     TRY_RC(dev_alloc(ctx, &w.dx_b, sizeof(float) * (size_t)(M * d)));
     TRY_RC(dev_alloc(ctx, &w.dvec, sizeof(float) * (size_t)(2 * BHS)));
@@ -321,10 +323,25 @@ void refresh_transposed(photon_ctx *ctx) {
     }
 }
 
+// Token ids index rows of the embedding and of its gradient and columns of the logits: an id
+// outside [0, vocab) would be an out-of-bounds access, so every id of a call is checked on the
+// device before any model kernel runs (one pass over the ids, one 4-byte read-back).
+int check_tokens(photon_ctx *ctx, const int32_t *tokens, int64_t count) {
+    ModelWorkspace &w = *ctx->ws;
+    hipStream_t st = ctx->stream;
+    token_range_check(st, tokens, count, ctx->cfg.vocab, w.tok_flag);
+    HIP_TRY(ctx, hipGetLastError());
+    int bad = 0;
+    HIP_TRY(ctx, hipMemcpyAsync(&bad, w.tok_flag, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    return bad ? PHOTON_EINVAL : PHOTON_OK;
+}
+
 template <typename T>
 int run_loss_grad(photon_ctx *ctx, const float *params, const int32_t *tokens, float *grads, float *loss) {
     ModelWorkspace &w = *ctx->ws;
     hipStream_t st = ctx->stream;
+    TRY_RC(check_tokens(ctx, tokens, (int64_t)ctx->micro_batch * (ctx->cfg.seq_len + 1)));
     if (sizeof(T) == 2) {
         convert_f32_to_bf16(st, params, w.w16, ctx->n);
         refresh_transposed(ctx);
@@ -356,6 +373,7 @@ int run_local_steps(photon_ctx *ctx, float *params, photon_opt_state *os, const 
             break;
         }
     const int n_groups = n_micro / group;
+    TRY_RC(check_tokens(ctx, tokens, (int64_t)n_steps * n_micro * mb_tokens));
     if (sizeof(T) == 2) {
         convert_f32_to_bf16(st, params, w.w16, ctx->n);
         refresh_transposed(ctx);

@@ -22,6 +22,12 @@ bool cfg_valid(const photon_model_cfg *c) {
     return true;
 }
 
+// [a, a + an) and [b, b + bn) share a byte
+bool overlaps(const void *a, int64_t an, const void *b, int64_t bn) {
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    return a && b && pa < pb + (uintptr_t)bn && pb < pa + (uintptr_t)an;
+}
+
 bool hp_valid(const photon_adamw_hp *hp) {
     return hp && hp->beta1 >= 0.f && hp->beta1 < 1.f && hp->beta2 >= 0.f && hp->beta2 < 1.f && hp->eps > 0.f &&
            hp->weight_decay >= 0.f;
@@ -81,6 +87,8 @@ void photon_destroy(photon_ctx *ctx) {
     if (!ctx) return;
     if (ctx->has_model) model_destroy(ctx);
     flat_free(ctx);
+    for (hipEvent_t e : ctx->timer.pool) (void)hipEventDestroy(e);
+    ctx->timer.pool.clear();
     delete ctx;
 }
 
@@ -152,9 +160,14 @@ int photon_aggregate(photon_ctx *ctx, float *global_params, const void *const *c
     if (!std::isfinite(oo->eta_s) || !std::isfinite(oo->mu)) return PHOTON_EINVAL;
     if (oo->mu != 0.f && !oo->momentum) return PHOTON_EINVAL;
     if (!aligned16(global_params) || !aligned16(oo->momentum)) return PHOTON_EINVAL;
+    // the kernel reads the client buffers while it rewrites the model and the momentum in place:
+    // none of them may share memory with either, nor those two with each other
+    const int64_t nb = ctx->n * 4, cb = ctx->n * (dtype == PHOTON_BF16 ? 2 : 4);
+    if (overlaps(global_params, nb, oo->momentum, nb)) return PHOTON_EINVAL;
     double sum = 0.0;
     for (int k = 0; k < K; ++k) {
-        if (!client_bufs[k] || !aligned16(client_bufs[k]) || client_bufs[k] == (const void *)global_params)
+        if (!client_bufs[k] || !aligned16(client_bufs[k])) return PHOTON_EINVAL;
+        if (overlaps(client_bufs[k], cb, global_params, nb) || overlaps(client_bufs[k], cb, oo->momentum, nb))
             return PHOTON_EINVAL;
         if (!std::isfinite(client_weights[k]) || client_weights[k] < 0.0) return PHOTON_EINVAL;
         sum += client_weights[k];
