@@ -94,8 +94,8 @@ def test_aggregate_matches_oracle_and_is_bit_reproducible(lib, K, kind, dtype, m
     if mu:
         assert rel_l2(a[1], ref_b) < 1e-6
     assert abs(a[2]["delta_norm2"] / ref_met["delta_norm2"] - 1) < 1e-5
-    if K <= 8 or kind == "deltas":
-        assert np.allclose(a[2]["client_norm2"], ref_met["client_norm2"], rtol=1e-5)
+    # per-client norms for every K and kind: taken against the model as it was before the step
+    assert np.allclose(a[2]["client_norm2"], ref_met["client_norm2"], rtol=1e-5)
 
 
 def test_fedavg_identities_on_gpu(lib):
@@ -132,6 +132,15 @@ def test_aggregate_rejects_bad_arguments(lib):
         lib.photon_aggregate(ctx, th, [c], lib.CLIENT_PARAMS, lib.BF16, [1.0], oo)
     with pytest.raises(lib.PhotonError):                       # misaligned pointer
         lib.photon_aggregate(ctx, th, [c[1:]], lib.CLIENT_PARAMS, lib.FP32, [1.0], oo)
+    # a client buffer that shares memory with the model or with the momentum buffer, or a momentum
+    # buffer that is the model: refused (the kernel rewrites both in place while reading clients)
+    mom = torch.zeros(n, device=DEV)
+    big = torch.zeros(2 * n, device=DEV)
+    for bufs, model, m_ in (([th], th, None), ([mom], th, mom), ([big[n - 8:2 * n - 8]], big[:n], None),
+                            ([c], th, th)):
+        with pytest.raises(lib.PhotonError):
+            lib.photon_aggregate(ctx, model, bufs, lib.CLIENT_PARAMS, lib.FP32, [1.0],
+                                 lib.OuterOpt(1.0, 0.5 if m_ is not None else 0.0, 0, lib._ptr(m_), 0))
     assert np.array_equal(th.cpu().numpy(), _vec("a", n))       # nothing was written
 
 
@@ -170,6 +179,28 @@ def test_clip_delta(lib):
         nrm = lib.photon_clip_delta(ctx, t, lib.FP32, max_norm)
         assert abs(nrm / ref_norm - 1) < 1e-6
         assert rel_l2(t.cpu().numpy(), O.clip_update(d.astype(np.float64), max_norm)) < 1e-6
+
+
+def test_clip_delta_bf16(lib):
+    """A bf16 pseudo-gradient is clipped in place: norm of the stored bf16 values; each element
+    scaled in float32 and rounded back to bf16 (ties to even), both decided in float32."""
+    n = 70003
+    d16 = bf16_round(_vec("d", n, 0.1))                      # the values a bf16 buffer holds
+    ctx = lib.photon_create_flat(n)
+    ref_norm = float(np.linalg.norm(d16.astype(np.float64)))
+    for max_norm in (ref_norm * 2, ref_norm / 4):
+        t = _dev(d16).to(torch.bfloat16)
+        nrm = lib.photon_clip_delta(ctx, t, lib.BF16, max_norm)
+        assert abs(nrm / ref_norm - 1) < 1e-6
+        got = t.float().cpu().numpy()
+        if max_norm > ref_norm:
+            assert np.array_equal(got, d16)                   # below the bound: untouched
+        else:
+            ref = O.clip_update(d16.astype(np.float64), max_norm)
+            assert rel_l2(got, ref) < 2.0 ** -8               # bf16 storage: half an ulp = 2^-9 relative per element
+            # element-wise: the float32 product with the float32 scale, rounded to bf16
+            sc = np.float32(max_norm / nrm)
+            assert np.array_equal(got, bf16_round(d16 * sc))
 
 
 def test_full_size_aggregate_sampled(lib):

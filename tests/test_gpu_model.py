@@ -296,3 +296,30 @@ def test_nonfinite_loss_is_reported_and_all_steps_run(lib):
         with pytest.raises(lib.PhotonError):
             lib.photon_client_local_steps(ctx, p2, st2, _dev(tok), 1, 1, bad, hp)
     assert st2.step == 3
+
+
+def test_token_ids_outside_the_vocabulary_are_refused_before_any_step(lib):
+    """Ids index embedding rows and logit columns; one id equal to the vocabulary size (or below
+    zero) must stop the call in its argument check, with nothing trained and nothing written."""
+    ms = configs.TINY.model
+    theta = _theta(ms)
+    tok = synth.client_token_batches(4, 0, 2, 1, 4, ms.seq_len, ms.vocab, perm_top=None)
+    ctx = lib.photon_create(lib.model_cfg(ms, "fp32"), 4)
+    hp = rounds.make_hp(configs.TINY)
+    for bad_id, where in ((ms.vocab, (1, 0, 3, ms.seq_len)), (-1, (0, 0, 0, 0))):
+        bad = tok.copy()
+        bad[where] = bad_id
+        p, m, v = _dev(theta), torch.zeros(theta.size, device=DEV), torch.zeros(theta.size, device=DEV)
+        st = lib.OptState(m.data_ptr(), v.data_ptr(), 0)
+        with pytest.raises(lib.PhotonError) as ei:
+            lib.photon_client_local_steps(ctx, p, st, _dev(bad), 2, 1, [1e-3] * 2, hp)
+        assert ei.value.status == lib.EINVAL and st.step == 0
+        assert np.array_equal(p.cpu().numpy(), theta) and not m.any()
+        g = torch.zeros(theta.size, device=DEV)
+        with pytest.raises(lib.PhotonError) as ei:
+            lib.photon_client_loss_grad(ctx, p, _dev(bad[where[0], 0]), g)
+        assert ei.value.status == lib.EINVAL and not g.any()
+    # the same batches with every id in range run
+    p, m, v = _dev(theta), torch.zeros(theta.size, device=DEV), torch.zeros(theta.size, device=DEV)
+    st = lib.OptState(m.data_ptr(), v.data_ptr(), 0)
+    assert len(lib.photon_client_local_steps(ctx, p, st, _dev(tok), 2, 1, [1e-3] * 2, hp)) == 2
