@@ -45,7 +45,8 @@ typedef enum {
     PHOTON_ENOMEM = -2,     /* workspace allocation failed */
     PHOTON_EHIP = -3,       /* a HIP call failed; raw code via photon_last_hip_error */
     PHOTON_ENONFINITE = -4, /* a step's loss was NaN or Inf (all steps were still run) */
-    PHOTON_ENOTIMPL = -5    /* combination not built */
+    PHOTON_ENOTIMPL = -5,   /* combination not built */
+    PHOTON_ELIMIT = -6      /* size beyond the fixed limit of photon_aggregate_static */
 } photon_status;
 
 typedef enum { PHOTON_FP32 = 0, PHOTON_BF16 = 1 } photon_dtype;
@@ -211,6 +212,35 @@ int photon_export_delta(photon_ctx *ctx, const float *global_params, const float
 int photon_aggregate(photon_ctx *ctx, float *global_params, const void *const *client_bufs, int32_t K,
                      int32_t kind, int32_t dtype, const double *client_weights,
                      photon_outer_opt *outer_opt, photon_agg_metrics *metrics);
+
+/*
+ * photon_aggregate for callers that cannot allocate device memory or synchronise: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same kernels and the
+ * same results as photon_aggregate, bit for bit, but no context: the only scratch the aggregation
+ * needs -- (K + 1) rows of 2048 float32 norm slots -- lives in a device array that is part of the
+ * library image, (PHOTON_STATIC_MAX_CLIENTS + 1) x 2048 x 4 bytes = 136 KiB on every GPU the
+ * library is used on, held until the process ends.  The call allocates nothing, frees nothing,
+ * copies nothing to the host and does not synchronise; it only enqueues kernels on hip_stream
+ * (a hipStream_t as void*, NULL = default stream) for the current device.
+ *   n               length of the vectors (>= 1).
+ *   global_params, client_bufs, kind, dtype, client_weights, outer_opt
+ *                   as for photon_aggregate (same checks, same PHOTON_EINVAL cases).
+ *   K               1 <= K <= PHOTON_STATIC_MAX_CLIENTS; a larger K (up to PHOTON_MAX_CLIENTS)
+ *                   returns PHOTON_ELIMIT and does nothing.
+ *   norms_out       DEVICE double[K + 1] or NULL: norms_out[0] = squared norm of the averaged
+ *                   pseudo-gradient, norms_out[1 + k] = client k's (the photon_agg_metrics values),
+ *                   written by the stream; the caller reads them after its own synchronisation.
+ *   hip_error_out   HOST, may be NULL: raw hipError_t when PHOTON_EHIP is returned, else 0.
+ * The first call on a device looks up the array's device address (hipGetSymbolAddress); make
+ * that call outside stream capture.  All calls on one GPU share the array: calls that overlap in
+ * time on the same GPU (different streams or threads) race on the norm slots -- theta and the
+ * momentum are still right, the norms are not -- so serialise them.  The array keeps the last
+ * call's contents; every slot a call reads is written by that call first, nothing needs clearing.
+ */
+#define PHOTON_STATIC_MAX_CLIENTS 16
+int photon_aggregate_static(void *hip_stream, int64_t n, float *global_params, const void *const *client_bufs,
+                            int32_t K, int32_t kind, int32_t dtype, const double *client_weights,
+                            photon_outer_opt *outer_opt, double *norms_out, int32_t *hip_error_out);
 
 /*
  * Global-norm clipping of one client update, the simplest member of the optional

@@ -16,10 +16,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libphoton.so")
 _lib = None
 
-OK, EINVAL, ENOMEM, EHIP, ENONFINITE, ENOTIMPL = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ENOMEM, EHIP, ENONFINITE, ENOTIMPL, ELIMIT = 0, -1, -2, -3, -4, -5, -6
 FP32, BF16 = 0, 1
 CLIENT_PARAMS, CLIENT_DELTAS = 0, 1
 MAX_CLIENTS = 64
+STATIC_MAX_CLIENTS = 16
 
 
 class ModelCfg(C.Structure):
@@ -97,6 +98,9 @@ def load(path: str | None = None):
     lib.photon_aggregate.restype = C.c_int
     lib.photon_aggregate.argtypes = [vp, vp, C.POINTER(vp), i32, i32, i32, C.POINTER(C.c_double),
                                      C.POINTER(OuterOpt), C.POINTER(AggMetrics)]
+    lib.photon_aggregate_static.restype = C.c_int
+    lib.photon_aggregate_static.argtypes = [vp, i64, vp, C.POINTER(vp), i32, i32, i32, C.POINTER(C.c_double),
+                                            C.POINTER(OuterOpt), vp, C.POINTER(i32)]
     lib.photon_clip_delta.restype = C.c_int
     lib.photon_clip_delta.argtypes = [vp, vp, i32, C.c_double, C.POINTER(C.c_double)]
     lib.photon_client_init.restype = C.c_int
@@ -211,6 +215,20 @@ def photon_aggregate(ctx: Ctx, global_params, client_bufs, kind: int, dtype: int
     if met is None:
         return None
     return {"delta_norm2": met.delta_norm2, "client_norm2": list(met.client_norm2[:k])}
+
+
+def photon_aggregate_static(stream: int, n: int, global_params, client_bufs, kind: int, dtype: int,
+                            client_weights: Sequence[float], outer_opt: OuterOpt, norms_out=None):
+    """norms_out: device float64 tensor of K + 1 elements, or None.  Enqueues only."""
+    lib = load()
+    k = len(client_bufs)
+    ptrs = (C.c_void_p * k)(*[_ptr(t) for t in client_bufs])
+    w = (C.c_double * k)(*client_weights)
+    hip = C.c_int32(0)
+    rc = lib.photon_aggregate_static(C.c_void_p(stream), n, _ptr(global_params), ptrs, k, kind, dtype, w,
+                                     C.byref(outer_opt), _ptr(norms_out), C.byref(hip))
+    if rc != OK:
+        raise PhotonError(rc, "photon_aggregate_static", int(hip.value))
 
 
 def photon_clip_delta(ctx: Ctx, delta, dtype: int, max_norm: float, want_norm: bool = True):

@@ -203,6 +203,8 @@ int flat_export_delta(photon_ctx *ctx, const float *global, const float *client,
                       int64_t n);
 int flat_aggregate(photon_ctx *ctx, float *global, const void *const *bufs, int K, int kind, int dtype,
                    const float *wnorm, photon_outer_opt *oo, photon_agg_metrics *metrics, int64_t n);
+int flat_aggregate_static(hipStream_t st, float *global, const void *const *bufs, int K, int kind, int dtype,
+                          const float *wnorm, photon_outer_opt *oo, double *norms_dev, int64_t n, int *hip_error);
 int flat_client_init(photon_ctx *ctx, const float *global, float *client, float *m, float *v, int64_t n);
 void fill_zero_f32(hipStream_t st, float *p, int64_t n);  // kernels_simple.hip
 int flat_clip(photon_ctx *ctx, void *delta, int dtype, double max_norm, double *norm_out, int64_t n);

@@ -9,6 +9,8 @@
 // squares go to one fixed slot per workgroup and are combined in slot order in float64,
 // so results are bit-identical between runs.
 
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -492,6 +494,57 @@ int flat_aggregate(photon_ctx *ctx, float *global, const void *const *bufs, int 
     HIP_TRY(ctx, hipStreamSynchronize(st));
     metrics->delta_norm2 = ctx->norm_host[0];
     for (int k = 0; k < PHOTON_MAX_CLIENTS; ++k) metrics->client_norm2[k] = k < K ? ctx->norm_host[k + 1] : 0.0;
+    return PHOTON_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Aggregation without a context and without any allocation: the norm slots live in a file-scope
+// device array instead of the context's workspace.  Each GPU holds its own copy of the array at
+// its own address; the address is looked up once per device, with that device current, and only
+// that pointer is ever handed to kernels (the array's name is a host-side stand-in in host code).
+
+static __device__ __align__(256) float scratch[(PHOTON_STATIC_MAX_CLIENTS + 1) * kBlocks];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float *g_scratch_ptr[kMaxDevices] = {};
+
+// device pointer of `scratch` on the current device; nullptr (and *err set) on failure
+float *scratch_on_current_device(hipError_t *err) {
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = static_cast<float *>(p);
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int flat_aggregate_static(hipStream_t st, float *global, const void *const *bufs, int K, int kind, int dtype,
+                          const float *wnorm, photon_outer_opt *oo, double *norms_dev, int64_t n, int *hip_error) {
+    hipError_t e = hipSuccess;
+    float *part = scratch_on_current_device(&e);
+    if (!part) {
+        if (hip_error) *hip_error = (int)e;
+        return PHOTON_EHIP;
+    }
+    aggregate_launches(st, global, bufs, K, kind, dtype, wnorm, oo, n, part, norms_dev);
+    e = hipGetLastError();
+    if (e != hipSuccess) {
+        if (hip_error) *hip_error = (int)e;
+        return PHOTON_EHIP;
+    }
+    oo->round += 1;
     return PHOTON_OK;
 }
 

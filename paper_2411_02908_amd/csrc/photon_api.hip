@@ -100,6 +100,7 @@ const char *photon_strerror(int status) {
         case PHOTON_EHIP: return "HIP runtime error";
         case PHOTON_ENONFINITE: return "non-finite loss";
         case PHOTON_ENOTIMPL: return "not implemented";
+        case PHOTON_ELIMIT: return "size beyond the limit of the allocation-free entry point";
         default: return "unknown status";
     }
 }
@@ -150,10 +151,12 @@ int photon_export_delta(photon_ctx *ctx, const float *global_params, const float
     return flat_export_delta(ctx, global_params, client_params, delta_out, dtype, ctx->n);
 }
 
-int photon_aggregate(photon_ctx *ctx, float *global_params, const void *const *client_bufs, int32_t K, int32_t kind,
-                     int32_t dtype, const double *client_weights, photon_outer_opt *oo, photon_agg_metrics *metrics) {
-    if (!ctx || !global_params || !client_bufs || !client_weights || !oo) return PHOTON_EINVAL;
-    if (K < 1 || K > PHOTON_MAX_CLIENTS) return PHOTON_EINVAL;
+// Argument checks shared by the two aggregation entry points; fills the normalised weights.
+static int aggregate_args_ok(int64_t n, const float *global_params, const void *const *client_bufs, int32_t K,
+                             int32_t max_clients, int32_t kind, int32_t dtype, const double *client_weights,
+                             const photon_outer_opt *oo, float *wnorm) {
+    if (!global_params || !client_bufs || !client_weights || !oo || n < 1) return PHOTON_EINVAL;
+    if (K < 1 || K > max_clients) return PHOTON_EINVAL;
     if (kind != PHOTON_CLIENT_PARAMS && kind != PHOTON_CLIENT_DELTAS) return PHOTON_EINVAL;
     if (dtype != PHOTON_FP32 && dtype != PHOTON_BF16) return PHOTON_EINVAL;
     if (kind == PHOTON_CLIENT_PARAMS && dtype != PHOTON_FP32) return PHOTON_EINVAL;
@@ -162,7 +165,7 @@ int photon_aggregate(photon_ctx *ctx, float *global_params, const void *const *c
     if (!aligned16(global_params) || !aligned16(oo->momentum)) return PHOTON_EINVAL;
     // the kernel reads the client buffers while it rewrites the model and the momentum in place:
     // none of them may share memory with either, nor those two with each other
-    const int64_t nb = ctx->n * 4, cb = ctx->n * (dtype == PHOTON_BF16 ? 2 : 4);
+    const int64_t nb = n * 4, cb = n * (dtype == PHOTON_BF16 ? 2 : 4);
     if (overlaps(global_params, nb, oo->momentum, nb)) return PHOTON_EINVAL;
     double sum = 0.0;
     for (int k = 0; k < K; ++k) {
@@ -173,10 +176,36 @@ int photon_aggregate(photon_ctx *ctx, float *global_params, const void *const *c
         sum += client_weights[k];
     }
     if (!(sum > 0.0) || !std::isfinite(sum)) return PHOTON_EINVAL;
-    float wnorm[PHOTON_MAX_CLIENTS];
     for (int k = 0; k < K; ++k) wnorm[k] = (float)(client_weights[k] / sum);  // normalised in float64
+    return PHOTON_OK;
+}
+
+int photon_aggregate(photon_ctx *ctx, float *global_params, const void *const *client_bufs, int32_t K, int32_t kind,
+                     int32_t dtype, const double *client_weights, photon_outer_opt *oo, photon_agg_metrics *metrics) {
+    if (!ctx) return PHOTON_EINVAL;
+    float wnorm[PHOTON_MAX_CLIENTS];
+    const int rc = aggregate_args_ok(ctx->n, global_params, client_bufs, K, PHOTON_MAX_CLIENTS, kind, dtype,
+                                     client_weights, oo, wnorm);
+    if (rc != PHOTON_OK) return rc;
     TimerScope ts(ctx);
     return flat_aggregate(ctx, global_params, client_bufs, K, kind, dtype, wnorm, oo, metrics, ctx->n);
+}
+
+int photon_aggregate_static(void *hip_stream, int64_t n, float *global_params, const void *const *client_bufs,
+                            int32_t K, int32_t kind, int32_t dtype, const double *client_weights,
+                            photon_outer_opt *oo, double *norms_out, int32_t *hip_error_out) {
+    if (hip_error_out) *hip_error_out = 0;
+    if (K > PHOTON_STATIC_MAX_CLIENTS && K <= PHOTON_MAX_CLIENTS) return PHOTON_ELIMIT;
+    if (norms_out && (reinterpret_cast<uintptr_t>(norms_out) & 7u)) return PHOTON_EINVAL;
+    float wnorm[PHOTON_MAX_CLIENTS];
+    const int rc = aggregate_args_ok(n, global_params, client_bufs, K, PHOTON_STATIC_MAX_CLIENTS, kind, dtype,
+                                     client_weights, oo, wnorm);
+    if (rc != PHOTON_OK) return rc;
+    int hip_error = 0;
+    const int rc2 = flat_aggregate_static((hipStream_t)hip_stream, global_params, client_bufs, K, kind, dtype, wnorm,
+                                          oo, norms_out, n, &hip_error);
+    if (hip_error_out) *hip_error_out = hip_error;
+    return rc2;
 }
 
 int photon_client_init(photon_ctx *ctx, const float *global_params, float *client_params, photon_opt_state *st) {
