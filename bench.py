@@ -186,7 +186,8 @@ def main() -> int:
     deltas = [torch.empty(n, dtype=ddt, device=dev) for _ in active]
     mom = torch.zeros_like(theta) if cfg.mu_s != 0.0 else None
     tokens = [torch.from_numpy(synth.client_token_batches(synth.MASTER_SEED, k, max(per_client[k], 1), cfg.n_micro,
-                                                          cfg.micro_batch, ms.seq_len, ms.vocab, cfg.zipf_s,
+                                                          cfg.micro_batch, ms.seq_len, ms.vocab,
+                                                          cfg.client_zipf_s(synth.MASTER_SEED, k),
                                                           cfg.perm_top)).to(dev) for k in range(K)]
     if cfg.weights == "dirichlet":
         weights = list(synth.dirichlet_weights(synth.stream_key(synth.MASTER_SEED, "weights"), K))

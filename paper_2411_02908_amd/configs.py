@@ -58,6 +58,7 @@ class RoundConfig:
     nesterov: bool = False
     weights: str = "uniform"  # "uniform" | "tokens" | "dirichlet"
     zipf_s: float = 1.1
+    zipf_s_range: tuple | None = None   # (lo, hi): every client draws its own exponent from its seed
     perm_top: float | None = 0.10
     recompute: int = 0
     micro_fuse: int = 1       # micro-batches the library may process as one pass (memory permitting)
@@ -65,6 +66,13 @@ class RoundConfig:
     @property
     def tokens_per_step(self) -> int:
         return self.micro_batch * self.n_micro * self.model.seq_len
+
+    def client_zipf_s(self, seed: int, client: int) -> float:
+        """Zipf exponent of one client's token stream."""
+        if self.zipf_s_range is None:
+            return self.zipf_s
+        from . import synth
+        return synth.client_zipf_exponent(seed, client, *self.zipf_s_range)
 
 
 TINY = RoundConfig(
@@ -103,7 +111,7 @@ B3 = RoundConfig(
     name="3B-bf16", dtype="bf16",
     model=ModelShape(32, 2560, 20, 10240, 50368, 2048),
     micro_batch=2, n_micro=1, clients=8, local_steps=8, lr=2e-3, lr_schedule="constant",
-    recompute=1)
+    recompute=1, zipf_s_range=(1.0, 1.3))
 
 B7 = RoundConfig(
     name="7B-bf16", dtype="bf16",

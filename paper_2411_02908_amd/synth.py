@@ -116,6 +116,12 @@ def client_token_batches(seed: int, client: int, n_steps: int, n_micro: int, mic
                        (n_steps, n_micro, micro_batch, seq_len + 1), vocab, s, perm)
 
 
+def client_zipf_exponent(seed: int, client: int, lo: float, hi: float) -> float:
+    """Per-client Zipf exponent, uniform in [lo, hi) from the client's own stream: clients whose
+    token streams differ in skew (heterogeneous data silos)."""
+    return float(lo + (hi - lo) * uniform(stream_key(seed, "zipf_s", client), 1)[0])
+
+
 def zipf_entropy(vocab: int, s: float) -> float:
     """Entropy (nats) of the unigram law: the floor of the loss on i.i.d. tokens."""
     p = np.arange(1, vocab + 1, dtype=np.float64) ** (-s)
@@ -150,10 +156,20 @@ def ln_gain_slices(n_layers: int, d: int, d_ff: int, vocab: int):
 
 
 def init_params(seed: int, n_layers: int, d: int, d_ff: int, vocab: int,
-                std: float = 0.02) -> np.ndarray:
-    """Flat float32 parameter vector: N(0, std^2) everywhere, LayerNorm gains = 1."""
+                std: float = 0.02, generator: str = "splitmix") -> np.ndarray:
+    """Flat float32 parameter vector: N(0, std^2) everywhere, LayerNorm gains = 1.
+
+    generator = "splitmix": this module's counter streams (Box-Muller), about 10 M values/s;
+    "philox": numpy's counter-based Philox bit generator keyed by the same stream key, about ten
+    times faster -- for the vectors of a billion parameters that full-depth cases need."""
     gains, n = ln_gain_slices(n_layers, d, d_ff, vocab)
-    theta = normal(stream_key(seed, "init"), n, std)
+    key = stream_key(seed, "init")
+    if generator == "philox":
+        rng = np.random.Generator(np.random.Philox(key=int(key)))
+        theta = rng.standard_normal(n, dtype=np.float32)
+        theta *= np.float32(std)
+    else:
+        theta = normal(key, n, std)
     for lo, hi in gains:
         theta[lo:hi] = 1.0
     return theta

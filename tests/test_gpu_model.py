@@ -189,9 +189,10 @@ def test_bf16_real_kernel_shapes_reduced_depth(lib, cfg, label):
 
 @pytest.mark.parametrize("cfg", [configs.B3, configs.B7], ids=["3B", "7B"])
 def test_full_size_large_models_one_step(lib, cfg):
-    """The 3B- and 7B-shaped configurations at their full depth and width, with their activation
-    recomputation policies: one optimizer step from zero AdamW state.  The oracle cannot run these
-    sizes, so the check is by properties that hold at any size: the loss at initialisation lies in
+    """Smoke check, not a parity test (parity of these shapes against the oracle is in
+    test_gpu_real_shapes.py): the 3B- and 7B-shaped configurations at their full depth and width, with
+    their activation recomputation policies, run one optimizer step from zero AdamW state within
+    the device's memory, and the result has the properties that hold at any size: the loss at initialisation lies in
     the band around ln V that the N(0, 0.02) init allows (tied head: the input token's own logit is
     the large one), and the first AdamW step moves every parameter by at most lr from its decayed
     value (|m_hat / (sqrt(v_hat) + eps)| <= 1), with most of them moving by almost exactly lr."""

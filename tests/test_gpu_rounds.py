@@ -159,6 +159,40 @@ def test_bf16_wide_shapes_and_recompute(lib, ms, recompute):
     assert max(errs.values()) < 3e-2, errs
 
 
+def test_3b_width_round_heterogeneous_zipf_streams(lib):
+    """The 3B-shaped round's structure at a size the oracle runs in seconds: K = 8 clients, each
+    with its own seeded Zipf exponent in [1.0, 1.3] (token streams of different skew: cross-entropy
+    with unbalanced, client-specific targets), micro-batch 2, per-block activation recomputation,
+    bf16 pseudo-gradients, plain FedAvg.  One block at the 3B width; a short sequence and a small
+    vocabulary.  Every client's first loss (identical parameters) at the bf16 tolerance, later
+    losses reported; the aggregation of the library's own pseudo-gradients at 1e-6."""
+    base = configs.B3
+    ms = ModelShape(1, base.model.d_model, base.model.n_heads, base.model.d_ff, 2000, 128)
+    cfg = replace(base, model=ms, local_steps=2, perm_top=None)
+    exps = [cfg.client_zipf_s(synth.MASTER_SEED, k) for k in range(cfg.clients)]
+    assert len(set(exps)) == cfg.clients and all(1.0 <= e < 1.3 for e in exps)
+    theta0 = synth.init_params(synth.MASTER_SEED, ms.n_layers, ms.d_model, ms.d_ff, ms.vocab)
+    batches = [synth.client_token_batches(synth.MASTER_SEED, k, cfg.local_steps, cfg.n_micro, cfg.micro_batch,
+                                          ms.seq_len, ms.vocab, exps[k], cfg.perm_top) for k in range(cfg.clients)]
+    lrs = configs.lr_array(cfg, cfg.local_steps)
+    weights = [1.0] * cfg.clients
+    out = rounds.run_round(cfg, theta0, batches, lrs, weights, DEV)
+    _, _, _, ref_losses, _ = O.federated_round(theta0.astype(np.float64), batches, lrs, ohp(cfg), oshape(ms), weights)
+    first = [abs(out["losses"][k][0] - ref_losses[k][0]) / ref_losses[k][0] for k in range(cfg.clients)]
+    later = [abs(out["losses"][k][1] - ref_losses[k][1]) / ref_losses[k][1] for k in range(cfg.clients)]
+    print("exponents", [f"{e:.3f}" for e in exps], "first-step loss errors", [f"{e:.1e}" for e in first],
+          "second-step (free-running)", [f"{e:.1e}" for e in later], flush=True)
+    assert max(first) < 1e-2
+    assert max(later) < 3e-2
+    # clients with more skewed streams start from a lower loss only through their targets: the
+    # losses must differ between clients (each saw its own stream)
+    assert len({round(l[0], 4) for l in out["losses"]}) == cfg.clients
+    ref_agg, _, ref_met = O.aggregate_deltas(theta0, [d.astype(np.float64) for d in out["deltas"]], weights)
+    assert rel_l2(out["theta"], ref_agg) < 1e-6
+    assert abs(out["metrics"]["delta_norm2"] / ref_met["delta_norm2"] - 1) < 1e-5
+    assert np.allclose(out["metrics"]["client_norm2"], ref_met["client_norm2"], rtol=1e-5)
+
+
 def test_sampled_profile_counts_every_launch_and_times_a_share(lib):
     """photon_profile_begin_sampled: every n-th launch of the GEMM / attention classes is timed, all are counted."""
     ms = ModelShape(2, 128, 2, 512, 1000, 64)

@@ -57,3 +57,22 @@ def test_config_shapes_and_flops():
     assert abs(configs.B1_3.model.flops_per_token() / 8.47e9 - 1) < 0.01
     lrs = configs.lr_array(configs.M125, 32)
     assert abs(lrs[0] - 6e-3) < 1e-12 and lrs[-1] < 1.1e-3 and all(x >= y for x, y in zip(lrs, lrs[1:]))
+
+
+def test_client_zipf_exponents_are_seeded_distinct_and_shape_the_stream():
+    """Heterogeneous token streams: every client draws its exponent in [lo, hi) from its own
+    stream; a larger exponent gives a more skewed unigram law (rank 1 more frequent, the share of
+    the closed form 1 / sum r^-s)."""
+    from paper_2411_02908_amd import configs
+    cfg = configs.B3
+    exps = [cfg.client_zipf_s(synth.MASTER_SEED, k) for k in range(cfg.clients)]
+    assert exps == [cfg.client_zipf_s(synth.MASTER_SEED, k) for k in range(cfg.clients)]
+    assert len(set(exps)) == cfg.clients and all(1.0 <= e < 1.3 for e in exps)
+    assert exps != [cfg.client_zipf_s(synth.MASTER_SEED + 1, k) for k in range(cfg.clients)]
+    assert configs.B1_3.client_zipf_s(synth.MASTER_SEED, 3) == 1.1            # homogeneous configurations
+    vocab = 5000
+    for k in (int(np.argmin(exps)), int(np.argmax(exps))):
+        tok = synth.zipf_tokens(synth.stream_key(1, "t", k), (200_000,), vocab, exps[k])
+        top = float(np.mean(tok == 0))
+        expect = 1.0 / float(np.sum(np.arange(1, vocab + 1, dtype=np.float64) ** -exps[k]))
+        assert abs(top - expect) < 4 * np.sqrt(expect * (1 - expect) / tok.size)
