@@ -125,56 +125,37 @@ def gemm_traffic(args, cfg):
     return GEMM_TRAFFIC["bytes_per_launch"] if digest == GEMM_TRAFFIC["source_sha256_16"] else None
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64,
-                    help="local optimizer steps in the timed round, all clients together (64 = the 4 x 16 of the workload)")
-    ap.add_argument("--warmup", type=int, default=1, help="untimed optimizer steps before the clock starts")
-    ap.add_argument("--config", default="1.3B-bf16")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--micro-fuse", type=int, default=-1,
-                    help="micro-batches of a step the library processes as one pass (default: the workload's setting)")
-    ap.add_argument("--no-kernel-events", action="store_true",
-                    help="leave the per-kernel HIP events out of the timed region (the roofline entries are then empty)")
-    ap.add_argument("--layers", type=int, default=0,
-                    help="counter runs only: keep this many blocks of the model (same kernel shapes, far fewer "
-                         "launches); the line it prints is marked and is not the headline figure")
-    ap.add_argument("--micro", type=int, default=0, help="counter runs only: micro-batches per step")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the K clients of a round run one after another on it and nothing "
-              "in this path uses a second GPU; run with --gpus 1", file=sys.stderr)
-        return 2
-
+def measure(cfg, steps: int, warmup: int, fuse: int, kernel_events: bool, log, trained_clients: int | None = None):
+    """One timed round of `cfg` on cuda:0: `steps` local optimizer steps spread over the clients
+    that are trained (all K, or the first `trained_clients` of them), each followed by its
+    pseudo-gradient export, then the aggregation over K buffers.  With trained_clients given the
+    round is run in two phases so that the largest configurations fit: the training buffers and
+    the model workspace are released before the K pseudo-gradient buffers of the aggregation are
+    completed (those of clients that were not trained are copies of the first one: the kernel's
+    time does not depend on the values), and only the training phase counts towards tokens/s."""
     import numpy as np
     import torch
 
     from paper_2411_02908_amd import binding as B
     from paper_2411_02908_amd import configs, synth
 
-    cfg = configs.ALL[args.config]
-    reduced = args.layers > 0 or args.micro > 0
-    if reduced:
-        import dataclasses
-        cfg = dataclasses.replace(configs.reduced_depth(cfg, args.layers or cfg.model.n_layers, cfg.micro_batch),
-                                  n_micro=args.micro or cfg.n_micro, name=cfg.name + " (reduced for counters)")
     ms = cfg.model
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    B.load()
     stream = torch.cuda.current_stream(dev).cuda_stream
-    fuse = cfg.micro_fuse if args.micro_fuse < 0 else max(1, args.micro_fuse)
     ctx = B.photon_create(B.model_cfg(ms, cfg.dtype, cfg.recompute, fuse), cfg.micro_batch, stream)
     n = ms.n_params
     K = cfg.clients
-    steps = max(args.steps, 1)
-    per_client = [steps // K + (1 if k < steps % K else 0) for k in range(K)]
+    two_phase = trained_clients is not None
+    kt = K if not two_phase else max(1, min(K, trained_clients))
+    per_client = [steps // kt + (1 if k < steps % kt else 0) if k < kt else 0 for k in range(K)]
     active = [k for k in range(K) if per_client[k] > 0]
 
     # ---- inputs, resident before timing
     gen = torch.Generator(device=dev).manual_seed(synth.MASTER_SEED)
-    theta = torch.randn(n, device=dev, generator=gen) * 0.02
+    theta = torch.empty(n, device=dev)
+    for lo in range(0, n, 1 << 30):           # in slices: no second full-size temporary
+        hi = min(n, lo + (1 << 30))
+        theta[lo:hi] = torch.randn(hi - lo, device=dev, generator=gen) * 0.02
     gains, _ = synth.ln_gain_slices(ms.n_layers, ms.d_model, ms.d_ff, ms.vocab)
     for lo, hi in gains:
         theta[lo:hi] = 1.0
@@ -184,63 +165,164 @@ def main() -> int:
     ddt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     dcode = B.BF16 if cfg.dtype == "bf16" else B.FP32
     deltas = [torch.empty(n, dtype=ddt, device=dev) for _ in active]
-    mom = torch.zeros_like(theta) if cfg.mu_s != 0.0 else None
-    tokens = [torch.from_numpy(synth.client_token_batches(synth.MASTER_SEED, k, max(per_client[k], 1), cfg.n_micro,
-                                                          cfg.micro_batch, ms.seq_len, ms.vocab,
-                                                          cfg.client_zipf_s(synth.MASTER_SEED, k),
-                                                          cfg.perm_top)).to(dev) for k in range(K)]
+    mom = torch.zeros_like(theta) if (cfg.mu_s != 0.0 and not two_phase) else None
+    tokens = {k: torch.from_numpy(synth.client_token_batches(synth.MASTER_SEED, k, per_client[k], cfg.n_micro,
+                                                             cfg.micro_batch, ms.seq_len, ms.vocab,
+                                                             cfg.client_zipf_s(synth.MASTER_SEED, k),
+                                                             cfg.perm_top)).to(dev) for k in active}
     if cfg.weights == "dirichlet":
         weights = list(synth.dirichlet_weights(synth.stream_key(synth.MASTER_SEED, "weights"), K))
     else:
-        weights = [float(per_client[k] * cfg.tokens_per_step) or 1.0 for k in range(K)]
+        weights = [1.0] * K
     hp = B.AdamWHP(cfg.beta1, cfg.beta2, cfg.adam_eps, cfg.weight_decay)
     lrs_all = configs.lr_array(cfg, max(per_client))
 
     # ---- warm-up (untimed): local steps on a scratch client, one export, one aggregation
     st = B.OptState(m.data_ptr(), v.data_ptr(), 0)
     B.photon_client_init(ctx, theta, client, st)
-    if args.warmup > 0:
-        wtok = tokens[0][:1].expand(args.warmup, -1, -1, -1).contiguous()
-        B.photon_client_local_steps(ctx, client, st, wtok, args.warmup, cfg.n_micro, [cfg.lr] * args.warmup, hp)
+    if warmup > 0:
+        wtok = tokens[active[0]][:1].expand(warmup, -1, -1, -1).contiguous()
+        B.photon_client_local_steps(ctx, client, st, wtok, warmup, cfg.n_micro, [cfg.lr] * warmup, hp)
         B.photon_export_delta(ctx, theta, client, deltas[0], dcode)
-        scratch = theta.clone()
-        smom = None if mom is None else torch.zeros_like(theta)
-        B.photon_aggregate(ctx, scratch, [deltas[0]], B.CLIENT_DELTAS, dcode, [1.0],
-                           B.OuterOpt(cfg.eta_s, cfg.mu_s, int(cfg.nesterov), B._ptr(smom), 0))
-        del scratch, smom
+        if not two_phase:
+            scratch = theta.clone()
+            smom = None if mom is None else torch.zeros_like(theta)
+            B.photon_aggregate(ctx, scratch, [deltas[0]], B.CLIENT_DELTAS, dcode, [1.0],
+                               B.OuterOpt(cfg.eta_s, cfg.mu_s, int(cfg.nesterov), B._ptr(smom), 0))
+            del scratch, smom
     torch.cuda.synchronize(dev)
-    print("bench: inputs resident, warm-up done", file=sys.stderr, flush=True)
+    log(f"bench: {cfg.name}: inputs resident, warm-up done")
 
     # ---- timed round
-    if not args.no_kernel_events:
+    if kernel_events:
         B.photon_profile_begin_sampled(ctx, event_stride(steps))
     losses = []
     torch.cuda.synchronize(dev)
     t0 = time.perf_counter()
     for i, k in enumerate(active):
-        print(f"bench: client {k}: {per_client[k]} local steps", file=sys.stderr, flush=True)
+        log(f"bench: {cfg.name}: client {k}: {per_client[k]} local steps")
         st = B.OptState(m.data_ptr(), v.data_ptr(), 0)
         B.photon_client_init(ctx, theta, client, st)
         losses.append(B.photon_client_local_steps(ctx, client, st, tokens[k], per_client[k], cfg.n_micro,
                                                   lrs_all[:per_client[k]], hp))
         B.photon_export_delta(ctx, theta, client, deltas[i], dcode)
-    oo = B.OuterOpt(cfg.eta_s, cfg.mu_s, int(cfg.nesterov), B._ptr(mom), 0)
-    metrics = B.photon_aggregate(ctx, theta, deltas, B.CLIENT_DELTAS, dcode, [weights[k] for k in active], oo)
+    metrics = None
+    if not two_phase:
+        oo = B.OuterOpt(cfg.eta_s, cfg.mu_s, int(cfg.nesterov), B._ptr(mom), 0)
+        metrics = B.photon_aggregate(ctx, theta, deltas, B.CLIENT_DELTAS, dcode, [weights[k] for k in active], oo)
     torch.cuda.synchronize(dev)
     elapsed = time.perf_counter() - t0
-    prof = B.photon_profile_end(ctx)
+    prof = B.photon_profile_end(ctx) if kernel_events else None
+    workspace = ctx.workspace_bytes
+    agg_clients = len(active)
+    if two_phase:
+        # second phase: the aggregation at the configuration's K, after the training buffers are gone
+        ctx.close()
+        del client, m, v, tokens
+        torch.cuda.empty_cache()
+        while len(deltas) < K:
+            d = torch.empty(n, dtype=ddt, device=dev)
+            d.copy_(deltas[0])
+            deltas.append(d)
+        mom = torch.zeros_like(theta) if cfg.mu_s != 0.0 else None
+        fctx = B.photon_create_flat(n, stream)
+        oo = B.OuterOpt(cfg.eta_s, cfg.mu_s, int(cfg.nesterov), B._ptr(mom), 0)
+        B.photon_aggregate(fctx, theta, deltas, B.CLIENT_DELTAS, dcode, weights, oo)      # warm-up, and a first
+        torch.cuda.synchronize(dev)                                                       # round of momentum
+        B.photon_profile_begin(fctx)
+        metrics = B.photon_aggregate(fctx, theta, deltas, B.CLIENT_DELTAS, dcode, weights, oo)
+        aprof = B.photon_profile_end(fctx)
+        fctx.close()
+        agg_clients = K
+        if prof is not None:
+            prof["agg_ms"], prof["agg_bytes"] = aprof["agg_ms"], aprof["agg_bytes"]
+    else:
+        ctx.close()
+    del theta, deltas, mom
+    torch.cuda.empty_cache()
+    return {"cfg": cfg, "elapsed": elapsed, "steps": steps, "per_client": per_client, "active": active, "prof": prof,
+            "losses": losses, "metrics": metrics, "workspace": workspace, "fuse": fuse, "agg_clients": agg_clients,
+            "two_phase": two_phase}
 
-    tokens_done = steps * cfg.tokens_per_step
-    tps = tokens_done / elapsed
-    gemm_tflops = prof["gemm_flops"] / (prof["gemm_ms"] * 1e-3) / 1e12 if prof["gemm_ms"] > 0 else 0.0
-    attn_tflops = prof["attn_flops"] / (prof["attn_ms"] * 1e-3) / 1e12 if prof["attn_ms"] > 0 else 0.0
-    adamw_gbps = prof["adamw_bytes"] / (prof["adamw_ms"] * 1e-3) / 1e9 if prof["adamw_ms"] > 0 else 0.0
-    agg_gbps = prof["agg_bytes"] / (prof["agg_ms"] * 1e-3) / 1e9 if prof["agg_ms"] > 0 else 0.0
-    delta_gbps = prof["delta_bytes"] / (prof["delta_ms"] * 1e-3) / 1e9 if prof["delta_ms"] > 0 else 0.0
-    # class totals: the timed launches' time scaled to all launches of the class
-    gemm_total_ms = prof["gemm_ms"] * prof["gemm_launches_total"] / max(1, prof["gemm_launches"])
-    attn_total_ms = prof["attn_ms"] * prof["attn_launches_total"] / max(1, prof["attn_launches"])
-    other_ms = elapsed * 1e3 - gemm_total_ms - attn_total_ms - prof["adamw_ms"] - prof["agg_ms"] - prof["delta_ms"]
+
+def rates(r) -> dict:
+    """Throughput and per-class rates of one measured round."""
+    cfg, prof, elapsed, steps = r["cfg"], r["prof"], r["elapsed"], r["steps"]
+    ms = cfg.model
+    tps = steps * cfg.tokens_per_step / elapsed
+    out = {"tokens_per_s": tps, "ms_per_step": elapsed * 1e3 / steps,
+           "mfu_causal": tps * ms.flops_per_token(True) / (PEAK_BF16_TFLOPS * 1e12)}
+    if prof is None:
+        return out
+
+    def rate(work, ms_):
+        return prof[work] / (prof[ms_] * 1e-3) if prof[ms_] > 0 else 0.0
+    out.update({
+        "gemm_TFLOPs": rate("gemm_flops", "gemm_ms") / 1e12, "attn_TFLOPs_causal": rate("attn_flops", "attn_ms") / 1e12,
+        "adamw_GBps": rate("adamw_bytes", "adamw_ms") / 1e9, "agg_GBps": rate("agg_bytes", "agg_ms") / 1e9,
+        "delta_GBps": rate("delta_bytes", "delta_ms") / 1e9,
+        # class totals: the timed launches' time scaled to all launches of the class
+        "gemm_total_ms": prof["gemm_ms"] * prof["gemm_launches_total"] / max(1, prof["gemm_launches"]),
+        "attn_total_ms": prof["attn_ms"] * prof["attn_launches_total"] / max(1, prof["attn_launches"])})
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64,
+                    help="local optimizer steps in the timed round, all clients together (64 = the 4 x 16 of the workload)")
+    ap.add_argument("--warmup", type=int, default=1, help="untimed optimizer steps before the clock starts")
+    ap.add_argument("--config", default="1.3B-bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="leave out the short runs of the other model sizes (125M, 3B, 7B) reported beside the headline")
+    ap.add_argument("--micro-fuse", type=int, default=-1,
+                    help="micro-batches of a step the library processes as one pass (default: the workload's setting)")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="leave the per-kernel HIP events out of the timed region (the roofline entries are then empty)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="counter runs only: keep this many blocks of the model (same kernel shapes, far fewer "
+                         "launches); the line it prints is marked and is not the headline figure")
+    ap.add_argument("--micro", type=int, default=0, help="counter runs only: micro-batches per step")
+    ap.add_argument("--trained-clients", type=int, default=0,
+                    help="train only this many of the K clients and run the aggregation as a second phase "
+                         "(what the 7B configuration needs to fit; default: all K in one phase)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the K clients of a round run one after another on it and nothing "
+              "in this path uses a second GPU; run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2411_02908_amd import binding as B
+    from paper_2411_02908_amd import configs, synth
+
+    def log(msg):
+        print(msg, file=sys.stderr, flush=True)
+
+    cfg = configs.ALL[args.config]
+    reduced = args.layers > 0 or args.micro > 0
+    if reduced:
+        import dataclasses
+        cfg = dataclasses.replace(configs.reduced_depth(cfg, args.layers or cfg.model.n_layers, cfg.micro_batch),
+                                  n_micro=args.micro or cfg.n_micro, name=cfg.name + " (reduced for counters)")
+    ms = cfg.model
+    torch.cuda.set_device(torch.device("cuda:0"))
+    B.load()
+    fuse = cfg.micro_fuse if args.micro_fuse < 0 else max(1, args.micro_fuse)
+    steps = max(args.steps, 1)
+    trained = args.trained_clients if args.trained_clients > 0 else (2 if cfg.name.startswith("7B") else None)
+    r = measure(cfg, steps, args.warmup, fuse, not args.no_kernel_events, log, trained)
+    q = rates(r)
+    prof = r["prof"] or {k: 0 for k in ("gemm_ms", "gemm_flops", "gemm_launches", "gemm_launches_total", "adamw_ms",
+                                        "adamw_launches", "agg_ms", "agg_bytes", "delta_ms")}
+    elapsed, per_client, active = r["elapsed"], r["per_client"], r["active"]
+    tps = q["tokens_per_s"]
+    gemm_tflops = q.get("gemm_TFLOPs", 0.0)
+    other_ms = elapsed * 1e3 - q.get("gemm_total_ms", 0.0) - q.get("attn_total_ms", 0.0) - prof["adamw_ms"] - \
+        (0.0 if r["two_phase"] else prof["agg_ms"]) - prof["delta_ms"]
 
     out = {
         "metric": "local_train_tokens_per_s",
@@ -258,33 +340,57 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: {ms.n_layers} blocks d={ms.d_model} heads={ms.n_heads} d_ff={ms.d_ff} "
                                f"vocab={ms.vocab} seq={ms.seq_len}; micro-batch {cfg.micro_batch} x {cfg.n_micro} "
                                f"accumulation = {cfg.tokens_per_step} tokens/step ({fuse} micro-batches per pass); K={len(active)} clients x "
-                               f"{per_client} local AdamW steps, bf16 pseudo-gradients, weighted FedAvg "
-                               f"(eta_s={cfg.eta_s}, mu_s={cfg.mu_s})",
-                   "params": n, "tokens_per_step": cfg.tokens_per_step, "clients": len(active),
+                               f"{[p for p in per_client if p]} local AdamW steps, bf16 pseudo-gradients, weighted FedAvg "
+                               f"over {r['agg_clients']} buffers (eta_s={cfg.eta_s}, mu_s={cfg.mu_s})"
+                               + ("; aggregation timed as a second phase, outside the tokens/s region" if r["two_phase"] else ""),
+                   "params": ms.n_params, "tokens_per_step": cfg.tokens_per_step, "clients": len(active),
                    "seed": synth.MASTER_SEED},
         "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": gemm_traffic(args, cfg),
+                     "traffic_source": "stored figure from rocprofv3 counter runs on this kernel source (profiles/), "
+                                       "not measured in this run; null when the source has changed since",
                      "kernel": "gemm_mfma_kernel (all operand/epilogue variants)",
                      "launches": prof["gemm_launches_total"], "launches_timed": prof["gemm_launches"],
                      "avg_launch_ms": prof["gemm_ms"] / max(1, prof["gemm_launches"]),
                      "flops_per_launch": prof["gemm_flops"] / max(1, prof["gemm_launches"])},
         "cpu_baseline": None,
         "model_flops_utilisation": {
-            "causal": tps * ms.flops_per_token(True) / (PEAK_BF16_TFLOPS * 1e12),
-            "full_attention_convention": tps * ms.flops_per_token(False) / (PEAK_BF16_TFLOPS * 1e12),
+            "causal": q["mfu_causal"],
+            "full_attention_convention_context_only": tps * ms.flops_per_token(False) / (PEAK_BF16_TFLOPS * 1e12),
             "peak_TFLOPs": PEAK_BF16_TFLOPS},
-        "aggregate": {"GBps": agg_gbps, "frac_of_hbm_peak": agg_gbps / PEAK_HBM_GBPS, "ms": prof["agg_ms"],
-                      "bytes": prof["agg_bytes"], "peak_GBps": PEAK_HBM_GBPS,
-                      "delta_norm2": metrics["delta_norm2"]},
-        "adamw": {"GBps": adamw_gbps, "frac_of_hbm_peak": adamw_gbps / PEAK_HBM_GBPS,
+        "aggregate": {"GBps": q.get("agg_GBps", 0.0), "frac_of_hbm_peak": q.get("agg_GBps", 0.0) / PEAK_HBM_GBPS,
+                      "ms": prof["agg_ms"], "bytes": prof["agg_bytes"], "peak_GBps": PEAK_HBM_GBPS,
+                      "clients": r["agg_clients"], "delta_norm2": r["metrics"]["delta_norm2"]},
+        "adamw": {"GBps": q.get("adamw_GBps", 0.0), "frac_of_hbm_peak": q.get("adamw_GBps", 0.0) / PEAK_HBM_GBPS,
                   "ms_per_launch": prof["adamw_ms"] / max(1, prof["adamw_launches"])},
-        "delta_export": {"GBps": delta_gbps, "frac_of_hbm_peak": delta_gbps / PEAK_HBM_GBPS},
-        "attention": {"TFLOPs_causal": attn_tflops, "frac_of_mfma_peak": attn_tflops / PEAK_BF16_TFLOPS},
-        "time_split_ms": {"gemm": gemm_total_ms, "attention": attn_total_ms, "adamw": prof["adamw_ms"],
-                          "aggregate": prof["agg_ms"], "delta_export": prof["delta_ms"], "other": other_ms},
-        "first_last_loss": [losses[0][0], losses[-1][-1]],
-        "workspace_GB": ctx.workspace_bytes / 1e9,
+        "delta_export": {"GBps": q.get("delta_GBps", 0.0), "frac_of_hbm_peak": q.get("delta_GBps", 0.0) / PEAK_HBM_GBPS},
+        "attention": {"TFLOPs_causal": q.get("attn_TFLOPs_causal", 0.0),
+                      "frac_of_mfma_peak": q.get("attn_TFLOPs_causal", 0.0) / PEAK_BF16_TFLOPS},
+        "time_split_ms": {"gemm": q.get("gemm_total_ms", 0.0), "attention": q.get("attn_total_ms", 0.0),
+                          "adamw": prof["adamw_ms"], "aggregate": prof["agg_ms"], "delta_export": prof["delta_ms"],
+                          "other": other_ms},
+        "first_last_loss": [r["losses"][0][0], r["losses"][-1][-1]],
+        "workspace_GB": r["workspace"] / 1e9,
     }
+    # ---- the other model sizes of the paper's shape table, a few steps each, beside the headline
+    if not args.no_other_configs and not reduced and args.config == "1.3B-bf16":
+        others = {}
+        for name, osteps in (("125M-bf16", 8), ("3B-bf16", 4), ("7B-bf16", 4)):
+            oc = configs.ALL[name]
+            ro = measure(oc, osteps, 1, oc.micro_fuse, not args.no_kernel_events, log, 2)
+            qo = rates(ro)
+            others[name] = {
+                "tokens_per_s": qo["tokens_per_s"], "ms_per_step": qo["ms_per_step"],
+                "tokens_per_step": oc.tokens_per_step, "steps": osteps, "recompute": oc.recompute,
+                "model_flops_utilisation_causal": qo["mfu_causal"],
+                "gemm_TFLOPs": qo.get("gemm_TFLOPs"), "attention_TFLOPs_causal": qo.get("attn_TFLOPs_causal"),
+                "adamw_GBps": qo.get("adamw_GBps"), "delta_export_GBps": qo.get("delta_GBps"),
+                "aggregate_GBps": qo.get("agg_GBps"), "aggregate_clients": ro["agg_clients"],
+                "aggregate_momentum": oc.mu_s != 0.0, "params": oc.model.n_params,
+                "workspace_GB": ro["workspace"] / 1e9,
+                "note": "2 of the K clients trained (1 untimed warm-up step, then the timed steps and exports); "
+                        "aggregation over K buffers timed as a second phase"}
+        out["other_configs"] = others
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
