@@ -60,11 +60,12 @@ void embedding_scatter_add(hipStream_t st, const float *dx0, const int32_t *toke
 template <typename T>
 void layernorm_fwd(hipStream_t st, const float *x, const float *gain, T *y, float *mean, float *rstd, int M, int d,
                    float eps);
-// dx_out = (dres ? dres : 0) + LN'(dy); dx16 (optional) = T(dx_out); dgain += column sums of dy * xhat.
+// dx_out = (dres ? dres : 0) + LN'(dy); dx16 (optional) = T(dx_out);
+// dgain = (accumulate ? dgain : 0) + column sums of dy * xhat.
 template <typename T>
 void layernorm_bwd(hipStream_t st, const T *dy, const float *x, const float *mean, const float *rstd,
-                   const float *gain, const float *dres, float *dx_out, T *dx16, float *dgain, float *scratch,
-                   int M, int d);
+                   const float *gain, const float *dres, float *dx_out, T *dx16, float *dgain, bool accumulate,
+                   float *scratch, int M, int d);
 int layernorm_bwd_scratch_floats(int d);
 
 // Causal ALiBi attention on packed qkv [M, 3d] (q | k | v, head h at columns h*Dh).

@@ -364,11 +364,11 @@ __global__ __launch_bounds__(256) void layernorm_bwd_wave_kernel(
     }
 }
 
-// out[c] += sum_r partial[r][c].  16 columns per workgroup (64-byte row pieces), 16 interleaved
+// out[c] = (accumulate ? out[c] : 0) + sum_r partial[r][c].  16 columns per workgroup (64-byte row pieces), 16 interleaved
 // row classes per column summed in increasing row order, classes then combined by a fixed tree:
 // a fixed summation order with d / 16 workgroups in flight.
 __global__ __launch_bounds__(256) void colsum_accum_kernel(const float *__restrict__ partial, int rows, int d,
-                                                            float *__restrict__ out) {
+                                                            float *__restrict__ out, bool accumulate) {
     __shared__ float red[16][17];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     const int c = blockIdx.x * 16 + tx;
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(256) void colsum_accum_kernel(const float *__restri
         if (ty < w) red[ty][tx] += red[ty + w][tx];
         __syncthreads();
     }
-    if (ty == 0 && c < d) out[c] += red[0][tx];
+    if (ty == 0 && c < d) out[c] = (accumulate ? out[c] : 0.f) + red[0][tx];
 }
 
 // ------------------------------------------------------------------------------------ attention (plain)
@@ -726,8 +726,8 @@ static void launch_ln_bwd_wave(hipStream_t st, const T *dy, const float *x, cons
 
 template <typename T>
 void layernorm_bwd(hipStream_t st, const T *dy, const float *x, const float *mean, const float *rstd,
-                   const float *gain, const float *dres, float *dx_out, T *dx16, float *dgain, float *scratch, int M,
-                   int d) {
+                   const float *gain, const float *dres, float *dx_out, T *dx16, float *dgain, bool accumulate,
+                   float *scratch, int M, int d) {
     int blocks = M < LN_BWD_BLOCKS ? M : LN_BWD_BLOCKS;
     bool wave_path = true;
     const int wblocks = (M + 3) / 4 < LN_BWD_BLOCKS ? (M + 3) / 4 : LN_BWD_BLOCKS;
@@ -744,12 +744,13 @@ void layernorm_bwd(hipStream_t st, const T *dy, const float *x, const float *mea
         hipLaunchKernelGGL((layernorm_bwd_kernel<T>), dim3(blocks), dim3(LN_THREADS), 0, st, dy, x, mean, rstd, gain,
                            dres, dx_out, dx16, scratch, M, d);
     }
-    hipLaunchKernelGGL(colsum_accum_kernel, dim3((d + 15) / 16), dim3(256), 0, st, scratch, blocks, d, dgain);
+    hipLaunchKernelGGL(colsum_accum_kernel, dim3((d + 15) / 16), dim3(256), 0, st, scratch, blocks, d, dgain,
+                       accumulate);
 }
 template void layernorm_bwd<float>(hipStream_t, const float *, const float *, const float *, const float *,
-                                   const float *, const float *, float *, float *, float *, float *, int, int);
+                                   const float *, const float *, float *, float *, float *, bool, float *, int, int);
 template void layernorm_bwd<bf16>(hipStream_t, const bf16 *, const float *, const float *, const float *,
-                                  const float *, const float *, float *, bf16 *, float *, float *, int, int);
+                                  const float *, const float *, float *, bf16 *, float *, bool, float *, int, int);
 
 template <typename T>
 void attention_fwd_simple(hipStream_t st, const T *qkv, T *o, float *lse, int B, int H, int S, int Dh) {

@@ -103,6 +103,8 @@ struct Runner {
     const T *wmat;        // matmul operands: params (fp32 mode) or the bf16 copy
     const T *wmat_t;      // transposed matrices (bf16 mode only)
     float *grads;
+    float beta = 1.f;     // 0 on the first pass of an optimizer step: gradients are overwritten, not
+                          // accumulated, so the accumulators need no clearing pass (and no read)
     int Bm, S, d, F, V, H, Dh, M;
 
     // batch: sequences per pass (the ctx micro-batch, or several of them fused)
@@ -164,34 +166,36 @@ struct Runner {
         T *dx16 = (T *)w.dx16, *dff = (T *)w.dff, *dtmp = (T *)w.dtmp, *dqkv = (T *)w.dqkv;
         // MLP: x'' = x' + GELU(b W1) W2
         GemmArgs g = ga(F, d, M, a.u, F, dx16, d, grads + L.w2[l], d);
-        g.beta = 1.f;
+        g.beta = beta;
         gemm<T>(st, GEMM_TN, EPI_ACCUM, g);
         g = ga(M, F, d, dx16, d, wmat + L.w2[l], d, dff, F);
         g.H = a.h;
         gemm<T>(st, GEMM_NT, EPI_DGELU, g);
         g = ga(d, F, M, a.b, d, dff, F, grads + L.w1[l], F);
-        g.beta = 1.f;
+        g.beta = beta;
         gemm<T>(st, GEMM_TN, EPI_ACCUM, g);
         gemm<T>(st, GEMM_NT, EPI_STORE, ga(M, d, F, dff, F, wmat + L.w1[l], F, dtmp, d));
         layernorm_bwd<T>(st, dtmp, a.x_mid, a.mean2, a.rstd2, params + L.g2[l], dx_in, dx_out, dx16,
-                         grads + L.g2[l], w.ln_scratch, M, d);
+                         grads + L.g2[l], beta != 0.f, w.ln_scratch, M, d);
         // attention: x' = x + Attn(LN(x) Wqkv) Wo        (dx_out now holds dL/dx')
         gemm<T>(st, GEMM_NT, EPI_STORE, ga(M, d, d, dx16, d, wmat + L.wo[l], d, dtmp, d));
         attention_bwd<T>(st, (const T *)a.qkv, (const T *)a.o, a.lse, dtmp, dqkv, w.dvec, Bm, H, S, Dh);
         // dWqkv and dWo together: dx16 (dL/dx') stays intact until the LayerNorm backward below
         g = ga(d, 3 * d, M, a.a, d, dqkv, 3 * d, grads + L.wqkv[l], 3 * d);
-        g.beta = 1.f;
+        g.beta = beta;
         GemmArgs go = ga(d, d, M, a.o, d, dx16, d, grads + L.wo[l], d);
-        go.beta = 1.f;
+        go.beta = beta;
         gemm_tn_accum_pair<T>(st, g, go);
         gemm<T>(st, GEMM_NT, EPI_STORE, ga(M, d, 3 * d, dqkv, 3 * d, wmat + L.wqkv[l], 3 * d, dtmp, d));
         // in-place on dx_out is safe: each element is read (as dres) and written by the same thread
         layernorm_bwd<T>(st, dtmp, x_in, a.mean1, a.rstd1, params + L.g1[l], dx_out, dx_out, dx16,
-                         grads + L.g1[l], w.ln_scratch, M, d);
+                         grads + L.g1[l], beta != 0.f, w.ln_scratch, M, d);
     }
 
-    // One micro-batch: accumulates gradients (scaled by grad_scale / M) into grads and
-    // loss_scale * mean loss into *loss_acc.
+    // One micro-batch: adds its gradients (scaled by grad_scale / M) to beta * grads -- every
+    // element of grads is written: the embedding by the head's weight-gradient product (before
+    // the scatter-add of the input rows), every matrix by its weight-gradient product, every
+    // gain by the LayerNorm backward -- and loss_scale * mean loss to *loss_acc.
     void micro_batch(const int32_t *tokens, float grad_scale, double loss_scale, double *loss_acc) {
         const Layout &L = w.lay;
         const int nl = c.n_layers;
@@ -209,12 +213,12 @@ struct Runner {
             cross_entropy_fwd_bwd<T>(st, z, w.ldz, V, tokens, S, m0, rows, w.loss_rows, grad_scale / (float)M);
             gemm_w(EPI_STORE, ga(rows, d, V, z, w.ldz, nullptr, 0, dy + (int64_t)m0 * d, d), L.E);
             GemmArgs g = ga(V, d, rows, z, w.ldz, y + (int64_t)m0 * d, d, grads + L.E, d);
-            g.beta = 1.f;
+            g.beta = m0 == 0 ? beta : 1.f;  // later chunks of the same pass always accumulate
             gemm<T>(st, GEMM_TN, EPI_ACCUM, g);
         }
         loss_reduce(st, w.loss_rows, M, loss_scale / (double)M, loss_acc);
         layernorm_bwd<T>(st, dy, w.x_in[nl], w.meanf, w.rstdf, params + L.gf, nullptr, w.dx_a, (T *)w.dx16,
-                         grads + L.gf, w.ln_scratch, M, d);
+                         grads + L.gf, beta != 0.f, w.ln_scratch, M, d);
 
         float *dx_cur = w.dx_a, *dx_nxt = w.dx_b;
         for (int l = nl - 1; l >= 0; --l) {
@@ -346,9 +350,9 @@ int run_loss_grad(photon_ctx *ctx, const float *params, const int32_t *tokens, f
         convert_f32_to_bf16(st, params, w.w16, ctx->n);
         refresh_transposed(ctx);
     }
-    fill_zero_f32(st, grads, ctx->n);
     fill_zero_f32(st, reinterpret_cast<float *>(w.loss_acc), 2);  // a fill kernel, not a memset node: safe under graph capture
     Runner<T> r(ctx, params, grads, ctx->micro_batch);
+    r.beta = 0.f;  // grads_out is overwritten
     r.micro_batch(tokens, 1.0f, 1.0, w.loss_acc);
     HIP_TRY(ctx, hipGetLastError());
     double host = 0.0;
@@ -384,11 +388,12 @@ int run_local_steps(photon_ctx *ctx, float *params, photon_opt_state *os, const 
         const int ns = (n_steps - s0) < w.loss_cap ? (n_steps - s0) : w.loss_cap;
         fill_zero_f32(st, reinterpret_cast<float *>(w.loss_acc), 2 * (int64_t)ns);
         for (int s = 0; s < ns; ++s) {
-            fill_zero_f32(st, w.grads, ctx->n);
             Runner<T> r(ctx, params, w.grads, ctx->micro_batch * group);
-            for (int j = 0; j < n_groups; ++j)
+            for (int j = 0; j < n_groups; ++j) {
+                r.beta = j == 0 ? 0.f : 1.f;  // the first pass of the step overwrites the accumulators
                 r.micro_batch(tokens + ((int64_t)(s0 + s) * n_micro + (int64_t)j * group) * mb_tokens,
                               1.0f / (float)n_groups, 1.0 / (double)n_groups, w.loss_acc + s);
+            }
             TRY_RC(flat_adamw(ctx, params, os->m, os->v, w.grads, ctx->n, os->step + 1, lrs[s0 + s], hp,
                               sizeof(T) == 2 ? w.w16 : nullptr));
             if (sizeof(T) == 2) refresh_transposed(ctx);
