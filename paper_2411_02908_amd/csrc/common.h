@@ -199,6 +199,12 @@ int flat_init(photon_ctx *ctx);
 void flat_free(photon_ctx *ctx);
 int flat_adamw(photon_ctx *ctx, float *p, float *m, float *v, const float *g, int64_t n, int64_t t,
                float lr, const photon_adamw_hp *hp, bf16 *w16);
+// AdamW over the matrices listed in a device table (flat_adamw_table), also writing the bf16 copy
+// and its per-matrix transpose; the table must cover every element of the vector exactly once.
+int flat_adamw_table(photon_ctx *ctx, const int64_t *offsets, const int *rows, const int *cols, int n_mats,
+                     void **table_out, int *tiles_out);
+int flat_adamw_tiled(photon_ctx *ctx, float *p, float *m, float *v, const float *g, int64_t n, int64_t t, float lr,
+                     const photon_adamw_hp *hp, bf16 *w16, bf16 *w16t, const void *table, int n_mats, int n_tiles);
 int flat_export_delta(photon_ctx *ctx, const float *global, const float *client, void *out, int dtype,
                       int64_t n);
 int flat_aggregate(photon_ctx *ctx, float *global, const void *const *bufs, int K, int kind, int dtype,

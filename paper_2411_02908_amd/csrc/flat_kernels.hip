@@ -9,7 +9,9 @@
 // squares go to one fixed slot per workgroup and are combined in slot order in float64,
 // so results are bit-identical between runs.
 
+#include <cmath>
 #include <mutex>
+#include <vector>
 
 #include "common.h"
 
@@ -72,6 +74,81 @@ __global__ __launch_bounds__(kThreads) void adamw_kernel(float *__restrict__ p, 
             v[i] = vv;
             if constexpr (W16) w16[i] = (bf16)pp;
         }
+    }
+}
+
+// AdamW over a set of row-major matrices of the flat vector, 64 x 64 tiles, writing besides the
+// updated parameters and moments the bf16 working copy (same layout) and its transpose
+// ([cols, rows] at the same offset of w16t) in the same pass: the forward products read the
+// transposed weights, and a separate transpose pass after every optimizer step would read and
+// write the whole bf16 copy once more.  A tile's rows are read and written as 256-byte row pieces;
+// the transposed tile goes through LDS so that its rows are written as 128-byte pieces.
+constexpr int AT = 64;  // tile edge
+struct AdamMatrix {
+    int64_t offset;      // first element in the flat vector
+    int rows, cols;
+    int tile_begin;      // index of the matrix's first tile among all tiles
+};
+__global__ __launch_bounds__(kThreads) void adamw_tiles_kernel(float *__restrict__ p, float *__restrict__ m,
+                                                                float *__restrict__ v, const float *__restrict__ g,
+                                                                bf16 *__restrict__ w16, bf16 *__restrict__ w16t,
+                                                                const AdamMatrix *__restrict__ mats, int n_mats,
+                                                                int n_tiles, AdamScalars s) {
+    __shared__ bf16 tile[AT][AT + 2];
+    for (int tix = blockIdx.x; tix < n_tiles; tix += gridDim.x) {
+        // the matrix this tile belongs to: tile_begin is increasing, a handful of entries per block
+        int lo = 0, hi = n_mats - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (mats[mid].tile_begin <= tix) lo = mid;
+            else hi = mid - 1;
+        }
+        const AdamMatrix mt = mats[lo];
+        const int tiles_c = (mt.cols + AT - 1) / AT;
+        const int r0 = ((tix - mt.tile_begin) / tiles_c) * AT, c0 = ((tix - mt.tile_begin) % tiles_c) * AT;
+        const int cq = (threadIdx.x & 15) * 4, rq = threadIdx.x >> 4;  // 4 columns, rows rq, rq + 16, ..
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int r = rq + 16 * k;
+            if (r0 + r < mt.rows && c0 + cq < mt.cols) {  // cols % 4 == 0: a quad is inside or outside as a whole
+                const int64_t i = mt.offset + (int64_t)(r0 + r) * mt.cols + c0 + cq;
+                f32x4 pp = ldg4(p + i), mm = ldg4(m + i), vv = ldg4(v + i), gg = ldg4(g + i);
+                bf16x4 o;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float pj = pp[j], mj = mm[j], vj = vv[j];
+                    adam_elem(pj, mj, vj, gg[j], s);
+                    pp[j] = pj;
+                    mm[j] = mj;
+                    vv[j] = vj;
+                    o[j] = (bf16)pj;
+                    tile[r][cq + j] = o[j];
+                }
+                stg4(p + i, pp);
+                stg4(m + i, mm);
+                stg4(v + i, vv);
+                *reinterpret_cast<bf16x4 *>(w16 + i) = o;
+            }
+        }
+        __syncthreads();
+        // transposed tile: row c of it = column c0 + c of the matrix, rows r0 .. r0 + 63
+        const int tr4 = (threadIdx.x & 15) * 4, tc = threadIdx.x >> 4;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int cc = tc + 16 * k;
+            if (c0 + cc < mt.cols && r0 + tr4 < mt.rows) {
+                bf16 *dst = w16t + mt.offset + (int64_t)(c0 + cc) * mt.rows + r0 + tr4;
+                if (mt.rows % 4 == 0) {
+                    bf16x4 o;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) o[j] = tile[tr4 + j][cc];
+                    *reinterpret_cast<bf16x4 *>(dst) = o;
+                } else {
+                    for (int j = 0; j < 4 && r0 + tr4 + j < mt.rows; ++j) dst[j] = tile[tr4 + j][cc];
+                }
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -401,8 +478,21 @@ void flat_free(photon_ctx *ctx) {
     ctx->norm_host = nullptr;
 }
 
+static AdamScalars adam_scalars(int64_t t, float lr, const photon_adamw_hp *hp);
+
 int flat_adamw(photon_ctx *ctx, float *p, float *m, float *v, const float *g, int64_t n, int64_t t, float lr,
                const photon_adamw_hp *hp, bf16 *w16) {
+    const AdamScalars s = adam_scalars(t, lr, hp);
+    TimedLaunch tl(ctx->stream, KC_ADAMW, (double)n * (w16 ? 30.0 : 28.0));
+    if (w16)
+        hipLaunchKernelGGL((adamw_kernel<true>), dim3(kBlocks), dim3(kThreads), 0, ctx->stream, p, m, v, g, w16, n, s);
+    else
+        hipLaunchKernelGGL((adamw_kernel<false>), dim3(kBlocks), dim3(kThreads), 0, ctx->stream, p, m, v, g, w16, n, s);
+    HIP_TRY(ctx, hipGetLastError());
+    return PHOTON_OK;
+}
+
+static AdamScalars adam_scalars(int64_t t, float lr, const photon_adamw_hp *hp) {
     AdamScalars s;
     s.b1 = hp->beta1;
     s.b2 = hp->beta2;
@@ -413,11 +503,33 @@ int flat_adamw(photon_ctx *ctx, float *p, float *m, float *v, const float *g, in
     s.decay = (float)(1.0 - (double)lr * (double)hp->weight_decay);
     s.inv_c1 = (float)(1.0 / (1.0 - pow((double)hp->beta1, (double)t)));
     s.inv_c2 = (float)(1.0 / (1.0 - pow((double)hp->beta2, (double)t)));
-    TimedLaunch tl(ctx->stream, KC_ADAMW, (double)n * (w16 ? 30.0 : 28.0));
-    if (w16)
-        hipLaunchKernelGGL((adamw_kernel<true>), dim3(kBlocks), dim3(kThreads), 0, ctx->stream, p, m, v, g, w16, n, s);
-    else
-        hipLaunchKernelGGL((adamw_kernel<false>), dim3(kBlocks), dim3(kThreads), 0, ctx->stream, p, m, v, g, w16, n, s);
+    return s;
+}
+
+// The matrices of the flat vector as the tiled kernel wants them (device table, built once).
+int flat_adamw_table(photon_ctx *ctx, const int64_t *offsets, const int *rows, const int *cols, int n_mats,
+                     void **table_out, int *tiles_out) {
+    std::vector<AdamMatrix> host(n_mats);
+    int tiles = 0;
+    for (int i = 0; i < n_mats; ++i) {
+        host[i] = AdamMatrix{offsets[i], rows[i], cols[i], tiles};
+        tiles += ((rows[i] + AT - 1) / AT) * ((cols[i] + AT - 1) / AT);
+    }
+    void *dev = nullptr;
+    if (hipMalloc(&dev, sizeof(AdamMatrix) * (size_t)n_mats) != hipSuccess) return PHOTON_ENOMEM;
+    HIP_TRY(ctx, hipMemcpy(dev, host.data(), sizeof(AdamMatrix) * (size_t)n_mats, hipMemcpyHostToDevice));
+    *table_out = dev;
+    *tiles_out = tiles;
+    return PHOTON_OK;
+}
+
+int flat_adamw_tiled(photon_ctx *ctx, float *p, float *m, float *v, const float *g, int64_t n, int64_t t, float lr,
+                     const photon_adamw_hp *hp, bf16 *w16, bf16 *w16t, const void *table, int n_mats, int n_tiles) {
+    const AdamScalars s = adam_scalars(t, lr, hp);
+    TimedLaunch tl(ctx->stream, KC_ADAMW, (double)n * 32.0);  // 16 B read, 12 + 2 + 2 B written per parameter
+    const int grid = n_tiles < 16 * kBlocks ? n_tiles : 16 * kBlocks;
+    hipLaunchKernelGGL(adamw_tiles_kernel, dim3(grid), dim3(kThreads), 0, ctx->stream, p, m, v, g, w16, w16t,
+                       (const AdamMatrix *)table, n_mats, n_tiles, s);
     HIP_TRY(ctx, hipGetLastError());
     return PHOTON_OK;
 }

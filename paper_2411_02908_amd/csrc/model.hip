@@ -67,6 +67,8 @@ struct ModelWorkspace {
     void *dx16 = nullptr, *dff = nullptr, *dqkv = nullptr, *dtmp = nullptr, *dy = nullptr;
     float *splitk = nullptr;
     size_t splitk_bytes = 0;
+    void *adam_table = nullptr;  // device table of the vector's matrices for the tiled AdamW (bf16 mode)
+    int adam_mats = 0, adam_tiles = 0;
 };
 
 namespace {
@@ -306,6 +308,24 @@ int alloc_workspace(photon_ctx *ctx) {
         const int64_t big = d * d > (int64_t)w.chunk * d ? d * d : (int64_t)w.chunk * d;
         w.splitk_bytes = sizeof(float) * (size_t)(8 * big);
         TRY_RC(dev_alloc(ctx, &w.splitk, w.splitk_bytes));
+        // every piece of the flat vector as a matrix: E [V, d], the weights, the gains as [1, d]
+        const Layout &L = w.lay;
+        std::vector<int64_t> off;
+        std::vector<int> rows, cols;
+        auto add = [&](int64_t o, int r, int cc) { off.push_back(o); rows.push_back(r); cols.push_back(cc); };
+        add(L.E, c.vocab, (int)d);
+        for (int l = 0; l < nl; ++l) {
+            add(L.g1[l], 1, (int)d);
+            add(L.wqkv[l], (int)d, (int)(3 * d));
+            add(L.wo[l], (int)d, (int)d);
+            add(L.g2[l], 1, (int)d);
+            add(L.w1[l], (int)d, (int)F);
+            add(L.w2[l], (int)F, (int)d);
+        }
+        add(L.gf, 1, (int)d);
+        w.adam_mats = (int)off.size();
+        TRY_RC(flat_adamw_table(ctx, off.data(), rows.data(), cols.data(), w.adam_mats, &w.adam_table, &w.adam_tiles));
+        w.allocs.push_back(w.adam_table);
     }
     return PHOTON_OK;
 }
@@ -394,9 +414,11 @@ int run_local_steps(photon_ctx *ctx, float *params, photon_opt_state *os, const 
                 r.micro_batch(tokens + ((int64_t)(s0 + s) * n_micro + (int64_t)j * group) * mb_tokens,
                               1.0f / (float)n_groups, 1.0 / (double)n_groups, w.loss_acc + s);
             }
-            TRY_RC(flat_adamw(ctx, params, os->m, os->v, w.grads, ctx->n, os->step + 1, lrs[s0 + s], hp,
-                              sizeof(T) == 2 ? w.w16 : nullptr));
-            if (sizeof(T) == 2) refresh_transposed(ctx);
+            if (sizeof(T) == 2)  // one pass: parameters, moments, the bf16 copy and its transposes
+                TRY_RC(flat_adamw_tiled(ctx, params, os->m, os->v, w.grads, ctx->n, os->step + 1, lrs[s0 + s], hp,
+                                        w.w16, w.w16t, w.adam_table, w.adam_mats, w.adam_tiles));
+            else
+                TRY_RC(flat_adamw(ctx, params, os->m, os->v, w.grads, ctx->n, os->step + 1, lrs[s0 + s], hp, nullptr));
             os->step += 1;
         }
         HIP_TRY(ctx, hipGetLastError());
