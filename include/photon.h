@@ -66,8 +66,11 @@ typedef struct {
     int32_t compute_dtype; /* photon_dtype: FP32 = everything in float32;
                               BF16 = bf16 matmul operands with fp32 accumulation, fp32 master
                               weights, fp32 residual stream, statistics and loss */
-    int32_t recompute;     /* 0 keep all activations; 1 keep block inputs, re-run each block's
-                              forward during backward; 2 same as 1 (full recomputation) */
+    int32_t recompute;     /* 0 keep all activations; 1 keep only every block's input and re-run each
+                              block's forward during backward (activation recomputation per block,
+                              which is also what "full" recomputation means when the block is the
+                              unit that is checkpointed); 2 is reserved for a coarser policy (inputs
+                              of every r-th block only) and photon_create returns PHOTON_ENOTIMPL */
     int32_t micro_fuse;    /* 0 or 1: every micro-batch of a step is a pass of its own.  G > 1: the
                               workspace holds G micro-batches and photon_client_local_steps runs the
                               micro-batches of a step g at a time as one batch, g = the largest

@@ -117,7 +117,7 @@ B7 = RoundConfig(
     name="7B-bf16", dtype="bf16",
     model=ModelShape(32, 4096, 32, 16384, 50368, 2048),
     micro_batch=1, n_micro=1, clients=8, local_steps=4, lr=1.2e-3, lr_schedule="constant",
-    mu_s=0.9, nesterov=True, recompute=2)
+    mu_s=0.9, nesterov=True, recompute=1)  # "full" recomputation = every block re-run, only block inputs kept
 
 ALL = {c.name: c for c in (TINY, M75, M125, M350, B1_3, B3, B7)}
 

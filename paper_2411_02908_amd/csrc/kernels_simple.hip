@@ -223,6 +223,58 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_fwd_kernel(const float *
     }
 }
 
+// One wavefront per row (d = 256 NI): the row lives in registers as NI float4 per lane, both
+// statistics are wave-level reductions (no workgroup barrier), all global traffic is 16 bytes per
+// lane.  Same arithmetic as layernorm_fwd_kernel: mean, then the variance of the centred values.
+template <typename T, int NI>
+__global__ __launch_bounds__(256) void layernorm_fwd_wave_kernel(const float *__restrict__ x,
+                                                                  const float *__restrict__ gain, T *__restrict__ y,
+                                                                  float *__restrict__ mean, float *__restrict__ rstd,
+                                                                  int M, float eps) {
+    constexpr int D = NI * 256;
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    const float *xr = x + (int64_t)m * D;
+    f32x4 v[NI];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        v[i] = *reinterpret_cast<const f32x4 *>(xr + 4 * (lane + 64 * i));
+        s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    }
+    const float mu = wave_sum(s) * (1.0f / (float)D);
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[i][k] -= mu;
+            q = fmaf(v[i][k], v[i][k], q);
+        }
+    const float rs = rsqrtf(wave_sum(q) * (1.0f / (float)D) + eps);
+    if (lane == 0) {
+        mean[m] = mu;
+        rstd[m] = rs;
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int c = 4 * (lane + 64 * i);
+        const f32x4 gn = *reinterpret_cast<const f32x4 *>(gain + c);
+        if constexpr (sizeof(T) == 2) {
+            bf16x4 o;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) o[k] = (bf16)(v[i][k] * rs * gn[k]);
+            *reinterpret_cast<bf16x4 *>(y + (int64_t)m * D + c) = o;
+        } else {
+            f32x4 o;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) o[k] = v[i][k] * rs * gn[k];
+            *reinterpret_cast<f32x4 *>(y + (int64_t)m * D + c) = o;
+        }
+    }
+}
+
 // Workgroup r walks rows r, r + G, ...; thread t owns columns t, t + 256, ... and keeps their
 // gain-gradient sums in registers; partial[r][c] is combined over r in order by colsum_kernel.
 template <typename T>
@@ -708,6 +760,15 @@ void embedding_scatter_add(hipStream_t st, const float *dx0, const int32_t *toke
 template <typename T>
 void layernorm_fwd(hipStream_t st, const float *x, const float *gain, T *y, float *mean, float *rstd, int M, int d,
                    float eps) {
+    const dim3 wgrid((M + 3) / 4), block(256);
+    switch (d) {  // the widths of the model table: one wave per row
+        case 768: hipLaunchKernelGGL((layernorm_fwd_wave_kernel<T, 3>), wgrid, block, 0, st, x, gain, y, mean, rstd, M, eps); return;
+        case 1024: hipLaunchKernelGGL((layernorm_fwd_wave_kernel<T, 4>), wgrid, block, 0, st, x, gain, y, mean, rstd, M, eps); return;
+        case 2048: hipLaunchKernelGGL((layernorm_fwd_wave_kernel<T, 8>), wgrid, block, 0, st, x, gain, y, mean, rstd, M, eps); return;
+        case 2560: hipLaunchKernelGGL((layernorm_fwd_wave_kernel<T, 10>), wgrid, block, 0, st, x, gain, y, mean, rstd, M, eps); return;
+        case 4096: hipLaunchKernelGGL((layernorm_fwd_wave_kernel<T, 16>), wgrid, block, 0, st, x, gain, y, mean, rstd, M, eps); return;
+        default: break;
+    }
     hipLaunchKernelGGL((layernorm_fwd_kernel<T>), dim3(M), dim3(LN_THREADS), 0, st, x, gain, y, mean, rstd, d, eps);
 }
 template void layernorm_fwd<float>(hipStream_t, const float *, const float *, float *, float *, float *, int, int, float);
@@ -736,6 +797,7 @@ void layernorm_bwd(hipStream_t st, const T *dy, const float *x, const float *mea
         case 1024: launch_ln_bwd_wave<T, 4>(st, dy, x, mean, rstd, gain, dres, dx_out, dx16, scratch, M, wblocks); break;
         case 2048: launch_ln_bwd_wave<T, 8>(st, dy, x, mean, rstd, gain, dres, dx_out, dx16, scratch, M, wblocks); break;
         case 2560: launch_ln_bwd_wave<T, 10>(st, dy, x, mean, rstd, gain, dres, dx_out, dx16, scratch, M, wblocks); break;
+        case 4096: launch_ln_bwd_wave<T, 16>(st, dy, x, mean, rstd, gain, dres, dx_out, dx16, scratch, M, wblocks); break;
         default: wave_path = false; break;
     }
     if (wave_path) {

@@ -68,6 +68,7 @@ int photon_create(const photon_model_cfg *cfg, int32_t micro_batch, void *hip_st
     if (!out) return PHOTON_EINVAL;
     *out = nullptr;
     if (!cfg_valid(cfg) || micro_batch < 1) return PHOTON_EINVAL;
+    if (cfg->recompute == 2) return PHOTON_ENOTIMPL;  // reserved: a policy coarser than per block
     photon_ctx *ctx = nullptr;
     int rc = create_common(photon_param_count(cfg), hip_stream, &ctx);
     if (rc != PHOTON_OK) return rc;

@@ -168,7 +168,7 @@ def test_bf16_benchmark_launch_configuration_against_oracle(lib):
 
 
 LARGE = [(configs.B3, "3B-shaped L=1, micro-batch 2, per-block recomputation"),
-         (configs.B7, "7B-shaped L=1, micro-batch 1, full recomputation")]
+         (configs.B7, "7B-shaped L=1, micro-batch 1, every block recomputed")]
 
 
 @pytest.mark.parametrize("full,label", LARGE, ids=["3B", "7B"])

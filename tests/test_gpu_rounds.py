@@ -136,7 +136,7 @@ WIDE_SHAPES = [
 ]
 
 
-WIDE_CASES = [(WIDE_SHAPES[0], 0), (WIDE_SHAPES[1], 0), (WIDE_SHAPES[1], 1), (WIDE_SHAPES[1], 2), (WIDE_SHAPES[2], 0)]
+WIDE_CASES = [(WIDE_SHAPES[0], 0), (WIDE_SHAPES[1], 0), (WIDE_SHAPES[1], 1), (WIDE_SHAPES[2], 0), (WIDE_SHAPES[2], 1)]
 
 
 @pytest.mark.parametrize("ms,recompute", WIDE_CASES, ids=[f"d{m.d_model}H{m.n_heads}-recompute{r}" for m, r in WIDE_CASES])
@@ -191,6 +191,17 @@ def test_3b_width_round_heterogeneous_zipf_streams(lib):
     assert rel_l2(out["theta"], ref_agg) < 1e-6
     assert abs(out["metrics"]["delta_norm2"] / ref_met["delta_norm2"] - 1) < 1e-5
     assert np.allclose(out["metrics"]["client_norm2"], ref_met["client_norm2"], rtol=1e-5)
+
+
+def test_reserved_recompute_policy_is_refused(lib):
+    """recompute = 2 is reserved for a policy coarser than per block: creating a context with it
+    reports 'not implemented' instead of silently running another policy."""
+    with pytest.raises(lib.PhotonError) as ei:
+        lib.photon_create(lib.model_cfg(configs.TINY.model, "fp32", 2), 4)
+    assert ei.value.status == lib.ENOTIMPL
+    with pytest.raises(lib.PhotonError) as ei:
+        lib.photon_create(lib.model_cfg(configs.TINY.model, "fp32", 3), 4)
+    assert ei.value.status == lib.EINVAL
 
 
 def test_sampled_profile_counts_every_launch_and_times_a_share(lib):
