@@ -267,6 +267,57 @@ def rates(r) -> dict:
     return out
 
 
+def hbm_ceiling(n: int) -> dict:
+    """What plain streaming kernels reach on this GPU for vectors of n float32, per read : write
+    mix, and the library's own bandwidth-bound kernels at the same length beside them."""
+    import torch
+
+    from paper_2411_02908_amd import binding as B
+
+    dev = torch.device("cuda:0")
+    B.load()
+    ctx = B.photon_create_flat(n, torch.cuda.current_stream(dev).cuda_stream)
+    src = torch.randn(4 * n, device=dev)
+    dst = torch.empty(4 * n, device=dev)
+    rows = []
+    for r, w in ((1, 0), (2, 0), (4, 0), (0, 1), (0, 3), (1, 1), (2, 1), (3, 1), (4, 1), (1, 3), (4, 3), (4, 4)):
+        ms = B.photon_stream_probe(ctx, r, w, src, dst, n, 10)
+        rows.append({"kernel": f"plain stream {r} read : {w} write", "GBps": 4.0 * n * (r + w) / ms / 1e6,
+                     "frac_of_hbm_peak": 4.0 * n * (r + w) / ms / 1e6 / PEAK_HBM_GBPS})
+    # the library's kernels on the same vectors (event-timed by the library)
+    p, m, v, g = (src[i * n:(i + 1) * n] for i in range(4))
+    w16 = dst[:n // 2 + 8].view(torch.bfloat16)[:n]
+    hp = B.AdamWHP(0.9, 0.95, 1e-8, 0.1)
+    st = B.OptState(m.data_ptr(), v.data_ptr(), 0)
+    v.abs_()
+    deltas = [dst[(k * n) // 2 + 16 * k:][:n // 2 + 8].view(torch.bfloat16)[:n] for k in range(8)]
+    for d in deltas:
+        d.normal_(0, 1e-3)
+    B.photon_profile_begin(ctx)
+    for _ in range(5):
+        B.photon_adamw_step(ctx, p, st, g, 1e-4, hp, None)
+    prof = B.photon_profile_end(ctx)
+    rows.append({"kernel": "AdamW (4 read : 3 write, no bf16 copy)", "GBps": prof["adamw_bytes"] / prof["adamw_ms"] / 1e6})
+    mom = src[3 * n:4 * n]
+    for K, mu in ((4, 0.0), (8, 0.0), (4, 0.9), (8, 0.9)):
+        B.photon_profile_begin(ctx)
+        for _ in range(5):
+            B.photon_aggregate(ctx, p, deltas[:K], B.CLIENT_DELTAS, B.BF16, [1.0] * K,
+                               B.OuterOpt(1.0, mu, int(mu != 0), B._ptr(mom) if mu else 0, 0), want_metrics=False)
+        prof = B.photon_profile_end(ctx)
+        rows.append({"kernel": f"aggregate K={K} bf16 pseudo-gradients, momentum {'on' if mu else 'off'}",
+                     "GBps": prof["agg_bytes"] / prof["agg_ms"] / 1e6})
+    B.photon_profile_begin(ctx)
+    for _ in range(5):
+        B.photon_export_delta(ctx, p, m, deltas[0], B.BF16)
+    prof = B.photon_profile_end(ctx)
+    rows.append({"kernel": "pseudo-gradient export (2 read : 0.5 write)", "GBps": prof["delta_bytes"] / prof["delta_ms"] / 1e6})
+    for row in rows:
+        row["frac_of_hbm_peak"] = row["GBps"] / PEAK_HBM_GBPS
+    ctx.close()
+    return {"hbm_streaming_ceiling": rows, "n": n, "peak_GBps": PEAK_HBM_GBPS}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -288,7 +339,14 @@ def main() -> int:
     ap.add_argument("--trained-clients", type=int, default=0,
                     help="train only this many of the K clients and run the aggregation as a second phase "
                          "(what the 7B configuration needs to fit; default: all K in one phase)")
+    ap.add_argument("--hbm-ceiling", action="store_true",
+                    help="instead of the round: streaming bandwidth of plain kernels per read : write mix and of the "
+                         "library's bandwidth-bound kernels, on vectors of the 1.3B model's length")
     args = ap.parse_args()
+    if args.hbm_ceiling and args.gpus == 1:
+        from paper_2411_02908_amd import configs
+        print(json.dumps(hbm_ceiling(configs.B1_3.model.n_params)))
+        return 0
     if args.gpus != 1:
         print("bench.py measures one GPU: the K clients of a round run one after another on it and nothing "
               "in this path uses a second GPU; run with --gpus 1", file=sys.stderr)

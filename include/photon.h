@@ -272,6 +272,21 @@ int photon_profile_begin_sampled(photon_ctx *ctx, int32_t every);
 /* Synchronises the stream, fills *out (HOST) and stops timing. */
 int photon_profile_end(photon_ctx *ctx, photon_profile *out);
 
+/*
+ * Measurement aid: what the memory system gives a plain streaming kernel shaped like the
+ * flat-vector kernels of this library (16 bytes per lane and access, 2048 workgroups in grid
+ * strides).  Every thread reads `reads` float32 vectors of length n (src, src + n, ...), adds them
+ * and writes the sum to `writes` vectors (dst, dst + n, ...); reads, writes in 0..4, not both 0.
+ * The mixes of the library's own kernels are 4 : 3.5 (AdamW), 2 : 0.5 (pseudo-gradient export),
+ * 1 : 3 (client start) and (K / 2 + 1) : 1 (aggregation of K bf16 pseudo-gradients).
+ *   src     DEVICE float32[reads * n] (may be NULL when reads == 0); dst DEVICE float32[max(writes, 1) * n]
+ *   n       multiple of 4;  repeats >= 1 timed launches after one untimed
+ *   ms_out  HOST double[1]: average milliseconds per launch; bytes moved = 4 n (reads + writes)
+ * Synchronises the ctx stream.
+ */
+int photon_stream_probe(photon_ctx *ctx, int32_t reads, int32_t writes, const float *src, float *dst, int64_t n,
+                        int32_t repeats, double *ms_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -105,6 +105,8 @@ def load(path: str | None = None):
     lib.photon_clip_delta.argtypes = [vp, vp, i32, C.c_double, C.POINTER(C.c_double)]
     lib.photon_client_init.restype = C.c_int
     lib.photon_client_init.argtypes = [vp, vp, vp, C.POINTER(OptState)]
+    lib.photon_stream_probe.restype = C.c_int
+    lib.photon_stream_probe.argtypes = [vp, i32, i32, vp, vp, i64, i32, C.POINTER(C.c_double)]
     lib.photon_profile_begin.restype = C.c_int
     lib.photon_profile_begin.argtypes = [vp]
     lib.photon_profile_begin_sampled.restype = C.c_int
@@ -241,6 +243,14 @@ def photon_clip_delta(ctx: Ctx, delta, dtype: int, max_norm: float, want_norm: b
 def photon_client_init(ctx: Ctx, global_params, client_params, opt_state: OptState):
     _check(_lib.photon_client_init(ctx.handle, _ptr(global_params), _ptr(client_params), C.byref(opt_state)),
            "photon_client_init", ctx.handle)
+
+
+def photon_stream_probe(ctx: Ctx, reads: int, writes: int, src, dst, n: int, repeats: int = 10) -> float:
+    """Average milliseconds per launch of the plain streaming kernel with the given read : write mix."""
+    ms = C.c_double(0)
+    _check(_lib.photon_stream_probe(ctx.handle, reads, writes, _ptr(src), _ptr(dst), n, repeats, C.byref(ms)),
+           "photon_stream_probe", ctx.handle)
+    return float(ms.value)
 
 
 def photon_profile_begin(ctx: Ctx):

@@ -41,7 +41,75 @@ TimedLaunch::~TimedLaunch() {
 TimerScope::TimerScope(photon_ctx *ctx) { g_timer = (ctx && ctx->timer.on) ? &ctx->timer : nullptr; }
 TimerScope::~TimerScope() { g_timer = nullptr; }
 
+// Plain streaming kernels for measuring what the memory system gives: 16 bytes per lane and
+// access, 2048 workgroups walking the vector in grid strides, as the flat-vector kernels do.
+namespace {
+typedef float probe_f4 __attribute__((ext_vector_type(4)));
+constexpr int kProbeBlocks = 2048, kProbeThreads = 256;
+
+// reads: r source arrays; writes: w destination arrays (r, w in 0..4, not both 0)
+template <int R, int W>
+__global__ __launch_bounds__(kProbeThreads) void stream_probe_kernel(const float *__restrict__ src, float *__restrict__ dst,
+                                                                      int64_t n, float *__restrict__ sink) {
+    const int64_t nvec = n >> 2;
+    const int64_t stride = (int64_t)gridDim.x * kProbeThreads;
+    probe_f4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t i = (int64_t)blockIdx.x * kProbeThreads + threadIdx.x; i < nvec; i += stride) {
+        probe_f4 v = {1.f, 2.f, 3.f, 4.f};
+#pragma unroll
+        for (int a = 0; a < R; ++a) v += *reinterpret_cast<const probe_f4 *>(src + (int64_t)a * n + 4 * i);
+#pragma unroll
+        for (int a = 0; a < W; ++a) *reinterpret_cast<probe_f4 *>(dst + (int64_t)a * n + 4 * i) = v;
+        if (W == 0) acc += v;
+    }
+    if (W == 0 && acc[0] + acc[1] + acc[2] + acc[3] == 12345.678f) sink[0] = acc[0];  // keeps the reads alive
+}
+
+template <int R>
+void launch_probe(int w, hipStream_t st, const float *src, float *dst, int64_t n, float *sink) {
+    const dim3 g(kProbeBlocks), b(kProbeThreads);
+    switch (w) {
+        case 0: hipLaunchKernelGGL((stream_probe_kernel<R, 0>), g, b, 0, st, src, dst, n, sink); break;
+        case 1: hipLaunchKernelGGL((stream_probe_kernel<R, 1>), g, b, 0, st, src, dst, n, sink); break;
+        case 2: hipLaunchKernelGGL((stream_probe_kernel<R, 2>), g, b, 0, st, src, dst, n, sink); break;
+        case 3: hipLaunchKernelGGL((stream_probe_kernel<R, 3>), g, b, 0, st, src, dst, n, sink); break;
+        default: hipLaunchKernelGGL((stream_probe_kernel<R, 4>), g, b, 0, st, src, dst, n, sink); break;
+    }
+}
+}  // namespace
+
 extern "C" {
+
+int photon_stream_probe(photon_ctx *ctx, int32_t reads, int32_t writes, const float *src, float *dst, int64_t n,
+                        int32_t repeats, double *ms_out) {
+    if (!ctx || !ms_out || reads < 0 || reads > 4 || writes < 0 || writes > 4 || reads + writes == 0) return PHOTON_EINVAL;
+    if (n < 4 || n % 4 != 0 || repeats < 1 || (reads && !src) || !dst) return PHOTON_EINVAL;
+    if (!aligned16(src) || !aligned16(dst)) return PHOTON_EINVAL;
+    hipStream_t st = ctx->stream;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    HIP_TRY(ctx, hipEventCreate(&e0));
+    HIP_TRY(ctx, hipEventCreate(&e1));
+    float *sink = dst;  // never written when writes == 0 (the condition in the kernel does not hold)
+    for (int rep = -1; rep < repeats; ++rep) {  // one untimed launch first
+        if (rep == 0) (void)hipEventRecord(e0, st);
+        switch (reads) {
+            case 0: launch_probe<0>(writes, st, src, dst, n, sink); break;
+            case 1: launch_probe<1>(writes, st, src, dst, n, sink); break;
+            case 2: launch_probe<2>(writes, st, src, dst, n, sink); break;
+            case 3: launch_probe<3>(writes, st, src, dst, n, sink); break;
+            default: launch_probe<4>(writes, st, src, dst, n, sink); break;
+        }
+    }
+    (void)hipEventRecord(e1, st);
+    hipError_t e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    HIP_TRY(ctx, e);
+    *ms_out = (double)ms / repeats;
+    return PHOTON_OK;
+}
 
 int photon_profile_begin_sampled(photon_ctx *ctx, int32_t every) {
     if (!ctx || every < 1) return PHOTON_EINVAL;

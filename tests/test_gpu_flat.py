@@ -262,3 +262,21 @@ def test_full_size_7b_aggregate_nesterov_sampled(lib):
     assert oo.round == 2
     exact = float(sum((deltas[0][lo:lo + (1 << 30)].double() ** 2).sum().item() for lo in range(0, n, 1 << 30)))
     assert abs(met["client_norm2"][0] / exact - 1) < 1e-5
+
+
+def test_stream_probe_moves_what_it_says_and_checks_its_arguments(lib):
+    """The measurement aid: with r reads and w writes every destination vector holds the sum of the
+    r sources plus the kernel's constant (1, 2, 3, 4 per group of four elements)."""
+    n = 4 * 100_003
+    ctx = lib.photon_create_flat(n)
+    src = torch.arange(3 * n, dtype=torch.float32, device=DEV) * 1e-3
+    dst = torch.zeros(2 * n, device=DEV)
+    ms = lib.photon_stream_probe(ctx, 3, 2, src, dst, n, 2)
+    assert ms > 0
+    want = src[:n] + src[n:2 * n] + src[2 * n:] + torch.tensor([1.0, 2.0, 3.0, 4.0], device=DEV).repeat(n // 4)
+    assert torch.allclose(dst[:n], want, rtol=1e-6) and torch.equal(dst[:n], dst[n:])
+    assert lib.photon_stream_probe(ctx, 2, 0, src, dst, n, 1) > 0          # read-only: dst untouched
+    assert torch.equal(dst[:n], dst[n:])
+    for bad in ((0, 0, n), (5, 1, n), (1, 5, n), (1, 1, n + 2)):
+        with pytest.raises(lib.PhotonError):
+            lib.photon_stream_probe(ctx, bad[0], bad[1], src, dst, bad[2], 1)
