@@ -24,14 +24,9 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// acc += a * b with the accumulator pinned to the accumulation registers.  The compiler's hazard
-// recogniser does not see inside inline assembly, so the wait states it would put between a
-// VALU write of an operand (the bf16 packing of b) and the MFMA reading it are spelled out.
-__device__ __forceinline__ void mfma_agpr(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
-    asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-
-// acc = 0, defined in the accumulation registers (0 * 0 + 0 through the matrix pipe)
+// acc = 0, defined in the accumulation registers (0 * 0 + 0 through the matrix pipe).  The compiler's hazard
+// recogniser does not see inside inline assembly, so the wait states it would put between the vector-ALU write
+// of the operand and the MFMA reading it are spelled out.
 __device__ __forceinline__ void mfma_agpr_zero(f32x16 &acc) {
     const bf16x8 z = {};
     asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
@@ -488,8 +483,30 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const bf16 *__rest
 }
 
 constexpr int BKB = 128;  // keys per workgroup (32 per wave)
-constexpr int BQT = 64;   // queries per tile
+constexpr int BQT = 64;   // queries per tile (two halves of 32)
 
+// s_waitcnt immediate: vmcnt = n (low four bits and bits 15:14), the other counters left alone
+constexpr int vmcnt_imm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
+
+// acc (+)= a * b, accumulator in the accumulation registers
+__device__ __forceinline__ void mfma_v(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma_v_first(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma_a(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// dK / dV for a block of 128 keys, walking the query tiles at or after it.  One wave per SIMD, so
+// nothing but this wave's own instruction stream can fill the matrix pipe while it does the
+// element-wise work: the loop is software-pipelined over half tiles of 32 queries.  In one step a
+// wave issues, interleaved slot by slot,
+//   A: the MFMAs of S = Q K^T and dP = dO V^T for the half tile after the current one,
+//   B: P = 2^(s - lse') and dS = P o (dP - D) for the current half tile (vector ALU),
+//   C: the MFMAs of dV += dO^T P and dK += Q^T dS for the half tile before it,
+// which are independent of each other inside the step.
 template <int DH>
 __global__ __launch_bounds__(256, 1) void flash_bwd_dkv_kernel(const bf16 *__restrict__ qkv,
                                                                 const bf16 *__restrict__ d_o,
@@ -498,18 +515,22 @@ __global__ __launch_bounds__(256, 1) void flash_bwd_dkv_kernel(const bf16 *__res
                                                                 bf16 *__restrict__ dqkv, int H, int S) {
     using T = Tile<DH>;
     constexpr int KS = DH / 16, DB = DH / 32;
-    __shared__ __attribute__((aligned(1024))) bf16 smem[2 * 2 * BQT * DH];  // [stage][Q | dO]
-    __shared__ __attribute__((aligned(256))) float stat[2][2][BQT];         // [stage][lseb | D][query]
+    constexpr int NST = 4;                    // tile stages in LDS
+    constexpr int NA = 2 * KS, NC = 4 * DB;   // MFMAs of stream A and of stream C per step
+    constexpr int PPS = (NA + NC) / 16;       // MFMAs per slot of a full step (16 slots = 16 result elements)
+    constexpr int RING = 8, DIST = 6;         // fragment ring and prefetch distance, in MFMAs
+    constexpr int TILE = BQT * DH;            // elements of one Q or dO tile
+    __shared__ __attribute__((aligned(1024))) bf16 smem[NST * 2 * TILE];  // [stage][Q | dO]
+    __shared__ __attribute__((aligned(256))) float stat[NST][2][BQT];     // [stage][lseb | D][query]
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // 1-D grid, key blocks in increasing order = decreasing number of query tiles
     const int nkb = (S + BKB - 1) / BKB;
     const int hb = blockIdx.x % (gridDim.x / nkb);
     const int hd = hb % H, b = hb / H;
     const int d = H * DH, ld = 3 * d;
     const int jb = (blockIdx.x / (gridDim.x / nkb)) * BKB, jw = jb + wave * 32;
-    const int kj = jw + (lane & 31);  // this lane's key
+    const int kj = jw + (lane & 31);
     const int kr = kj < S ? kj : S - 1;
     const bf16 *base = qkv + (int64_t)b * S * ld;
     const bf16 *gbase = d_o + (int64_t)b * S * d;
@@ -517,125 +538,231 @@ __global__ __launch_bounds__(256, 1) void flash_bwd_dkv_kernel(const bf16 *__res
     const rsrc_t rg = make_rsrc(gbase, (uint32_t)((int64_t)S * d * 2));
     const float slope2 = exp2f(-8.0f * (float)(hd + 1) / (float)H) * kLog2e;
     const float scale = rsqrtf((float)DH), scale2 = scale * kLog2e;
-    const rsrc_t rl = make_rsrc(lseb + ((int64_t)b * H + hd) * S, (uint32_t)(S * 4));
-    const rsrc_t rd = make_rsrc(dvec + ((int64_t)b * H + hd) * S, (uint32_t)(S * 4));
+    // waves 0, 2 copy the tile's lseb, waves 1, 3 its D (the same bytes twice: every wave issues the
+    // same number of copies, so one wait count serves all)
+    const float *sp_ = ((wave & 1) ? dvec : lseb) + ((int64_t)b * H + hd) * S;
+    const rsrc_t rs = make_rsrc(sp_, (uint32_t)(S * 4));
 
-    // K^T and V^T operands: lane = key, 8 consecutive dh per k-step
+    // K^T and V^T operands (lane = key, 8 consecutive dh per k-step) live in the accumulation registers for the
+    // whole kernel: loaded there directly, read from there by the MFMAs
     bf16x8 kf[KS], vf[KS];
     {
         const bf16 *kp = base + (int64_t)kr * ld + d + hd * DH + 8 * (lane >> 5);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = *reinterpret_cast<const bf16x8 *>(kp + 16 * ks);
-            vf[ks] = *reinterpret_cast<const bf16x8 *>(kp + d + 16 * ks);
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(kf[ks]) : "v"(kp + 16 * ks) : "memory");
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(vf[ks]) : "v"(kp + d + 16 * ks) : "memory");
         }
+        // (no wait here: loads retire in order, so the wait for the first tile's copies below covers these)
     }
-    f32x16 dk[DB], dv[DB];  // pinned to the accumulation registers: only inline assembly touches them
+    f32x16 dk[DB], dv[DB];
 #pragma unroll
     for (int i = 0; i < DB; ++i) {
         mfma_agpr_zero(dk[i]);
         mfma_agpr_zero(dv[i]);
     }
-    const float ckj = slope2 * (float)kj;  // key part of the bias; the query part is folded into lseb
+    const float ckj = slope2 * (float)kj;
 
-    const int t0 = jb / BQT, t1 = S / BQT;  // query tiles at or after the block's first key
-    auto issue = [&](int t, int stage) {
-        bf16 *qs = smem + stage * 2 * BQT * DH;
-        T::template copy<BQT>(rq, t * BQT, ld * 2, hd * DH * 2, qs, wave, lane);
-        T::template copy<BQT>(rg, t * BQT, d * 2, hd * DH * 2, qs + BQT * DH, wave, lane);
-        // log-sum-exp and D of the tile's 64 queries: 256 bytes each, copied straight to LDS as
-        // well (a register round trip would make the wave wait for the load before it computes)
-        if (wave == 0)
-            copy4_to_lds(rl, lds_addr(&stat[stage][0][0]), lane * 4, t * BQT * 4);
-        else if (wave == 1)
-            copy4_to_lds(rd, lds_addr(&stat[stage][1][0]), lane * 4, t * BQT * 4);
-    };
-    issue(t0, 0);
-    for (int t = t0; t < t1; ++t) {
-        const int stage = (t - t0) & 1;
-        __builtin_amdgcn_s_waitcnt(0x0f70);
-        __syncthreads();
-        if (t + 1 < t1) issue(t + 1, stage ^ 1);
-        const int i0 = t * BQT;
-        if (i0 + BQT - 1 < jw) continue;  // every query of the tile precedes every key of this wave
-        const bf16 *qt = smem + stage * 2 * BQT * DH;
-        const bf16 *gt = qt + BQT * DH;
-        const bool diag = i0 < jw + 31;
-        const int thr = kj - i0 - 4 * (lane >> 5);  // key > query i0 + 32 qb + crow(e)  <=>  erow(e) < thr - 32 qb
-        f32x16 sp[4];  // S block 0, S block 1, dP block 0, dP block 1 (rows = queries, lane = key);
-                       // P overwrites S and dS overwrites dP, which keeps the working set in the 256
-                       // architectural registers and the dK / dV accumulators parked in the AGPRs
+    const int t0 = jb / BQT, t1 = S / BQT;
+    // global -> LDS copies of tile t, one instruction at a time (CI = 0 .. NCP - 1: Q rows, dO rows; NCP: statistics).
+    // A tile index past the last one turns every lane's offset out of range: nothing is read.
+    constexpr int NCP = 2 * (BQT / T::ROWS_PER_INST / 4);
+    int voffq[NCP / 2], voffg[NCP / 2];
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) sp[r][e] = 0.f;
-        {
-            const bf16 *const tiles[4] = {qt, qt, gt, gt};
-            const int bases[4] = {0, 32, 0, 32};
-            const bf16x8 *const bs[4] = {kf, kf, vf, vf};
-            T::template rows_product<4>(tiles, bases, bs, sp, lane);
+    for (int c = 0; c < NCP / 2; ++c) {
+        const int inst = wave * (NCP / 2) + c;
+        const int r = inst * T::ROWS_PER_INST + lane / T::NC;
+        const int cc = (lane % T::NC) ^ T::swz(r);
+        voffq[c] = (lane / T::NC) * ld * 2 + cc * 16;
+        voffg[c] = (lane / T::NC) * d * 2 + cc * 16;
+    }
+    auto copy_one = [&](auto ci_, int t, int stage) {
+        constexpr int CI = decltype(ci_)::value;
+        const bool valid = t < t1;
+        if constexpr (CI < NCP) {
+            constexpr int c = CI % (NCP / 2);
+            constexpr bool G = CI >= NCP / 2;
+            const int inst = wave * (NCP / 2) + c;
+            bf16 *dst = smem + stage * 2 * TILE + (G ? TILE : 0);
+            const int row = t * BQT + inst * T::ROWS_PER_INST;
+            const int v = valid ? (G ? voffg[c] : voffq[c]) : 0x7fffffff;
+            copy16_to_lds(G ? rg : rq, lds_addr(dst) + inst * 1024, v, row * (G ? d : ld) * 2 + hd * DH * 2);
+        } else {
+            copy4_to_lds(rs, lds_addr(&stat[stage][wave & 1][0]), valid ? lane * 4 : 0x7fffffff, t * BQT * 4);
         }
-        // P = 2^(s - lseb + slope * key) and dS = P o (dP - D); the masked form only for tiles on the
-        // diagonal, where some keys lie after some queries (integer test: exact)
-        auto softmax_grad = [&](auto diag_) {
-            constexpr bool DIAG = decltype(diag_)::value;
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                f32x16 &sacc = sp[qb];
-                f32x16 &pacc = sp[2 + qb];
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const int r0 = qb * 32 + 8 * e4 + 4 * (lane >> 5);
-                    const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&stat[stage][0][r0]);  // lseb, log2 units
-                    const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&stat[stage][1][r0]);
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const int e = 4 * e4 + x;
-                        float pe = fast_exp2(fmaf(sacc[e], scale2, ckj) - l4[x]);
-                        if (DIAG && erow(e) < thr - 32 * qb) pe = 0.f;
-                        sacc[e] = pe;
-                        pacc[e] = pe * (pacc[e] - d4[x]);
+    };
+    auto copy_tile = [&](int t, int stage) {
+        static_for<0, NCP + 1>([&](auto ci_) { copy_one(ci_, t, stage); });
+    };
+
+    f32x16 sS[2], sP[2];       // [half] scores and dP of the half tile computed by A, consumed by B one step later
+    bf16x8 pkP[2][2], pkS[2][2];  // [half][16-query step] P and dS as bf16 B operands, written by B, consumed by C
+    bf16x8 fr[RING];
+    f32x4 l4[2], d4[2];
+
+    // fragment of MFMA number J of stream A (S, dP of half HALF of the tile at qt / gt) or C
+    auto frag_a = [&](auto j_, auto half_, const bf16 *qt) {
+        constexpr int J = decltype(j_)::value, HALF = decltype(half_)::value;
+        return T::frag_rows((J & 1) ? qt + TILE : qt, 32 * HALF, J >> 1, lane);
+    };
+    auto frag_c = [&](auto j_, auto half_, const bf16 *qt) {
+        constexpr int J = decltype(j_)::value, HALF = decltype(half_)::value;
+        constexpr int kkl = J / (2 * DB), typ = (J / DB) & 1, i = J % DB;
+        return T::template frag_cols<16 * (2 * HALF + kkl)>(typ ? qt : qt + TILE, i * 32, lane);
+    };
+
+    // One step.  ODD = second half of tile t.  Streams present: HA, HB, HC.  NEXT_* describe the step that
+    // follows (its first DIST fragments are requested here).  Tiles: ta = tile of stream A, tb = B's, tc = C's.
+    //   even step (tile t):  A half 1 of t,     B half 0 of t,  C half 1 of t - 1
+    //   odd  step (tile t):  A half 0 of t + 1, B half 1 of t,  C half 0 of t;   copies of tile t + 3
+    float hold_p = 0.f, hold_s = 0.f;
+    auto stat_read = [&](auto g_, int stage, int half) {
+        constexpr int G = decltype(g_)::value;
+        const int r0 = half * 32 + 8 * (G & 3) + 4 * (lane >> 5);
+        l4[G & 1] = *reinterpret_cast<const f32x4 *>(&stat[stage][0][r0]);
+        d4[G & 1] = *reinterpret_cast<const f32x4 *>(&stat[stage][1][r0]);
+    };
+    auto step = [&](auto odd_, auto ha_, auto hb_, auto hc_, auto pre_, auto nxt_, auto mask_, int t) __attribute__((always_inline)) {
+        constexpr bool ODD = decltype(odd_)::value, HA = decltype(ha_)::value, HB = decltype(hb_)::value,
+                       HC = decltype(hc_)::value, PRE = decltype(pre_)::value, NXT = decltype(nxt_)::value,
+                       MASK = decltype(mask_)::value;
+        constexpr int HALF_A = ODD ? 0 : 1, HALF_B = ODD ? 1 : 0, HALF_C = ODD ? 0 : 1;
+        constexpr int NM = (HA ? NA : 0) + (HC ? NC : 0);
+        constexpr int C_FIRST = (ODD && HA) ? NC * 3 / 4 : 0;  // C MFMAs ahead of stream A in this step
+        const int sa = ((ODD ? t + 1 : t) - t0) & (NST - 1), sb = (t - t0) & (NST - 1),
+                  sc = ((ODD ? t : t - 1) - t0) & (NST - 1);
+        const bf16 *qa = smem + sa * 2 * TILE, *qc = smem + sc * 2 * TILE;
+        // position p of this step -> (is stream A, index in its stream)
+        auto is_a = [](int p) constexpr { return HA && (!HC || (ODD ? (p >= C_FIRST && p < C_FIRST + NA) : p < NA)); };
+        auto idx = [](int p) constexpr {
+            if (!HC) return p;
+            if (!HA) return p;
+            if (ODD) return p < C_FIRST ? p : (p < C_FIRST + NA ? p - C_FIRST : p - NA);
+            return p < NA ? p : p - NA;
+        };
+        auto request = [&](auto p_) {
+            constexpr int P = decltype(p_)::value;
+            if constexpr (P < NM) {
+                if constexpr (is_a(P)) fr[P % RING] = frag_a(std::integral_constant<int, idx(P)>{}, std::integral_constant<int, HALF_A>{}, qa);
+                else fr[P % RING] = frag_c(std::integral_constant<int, idx(P)>{}, std::integral_constant<int, HALF_C>{}, qc);
+            } else if constexpr (NXT) {
+                // the next step is the other kind with all three streams: even starts with A (half 1 of tile t + 1,
+                // seen from an odd step), odd starts with C (half 0 of tile t, seen from an even step)
+                constexpr int Q = P - NM;
+                if constexpr (ODD) fr[P % RING] = frag_a(std::integral_constant<int, Q>{}, std::integral_constant<int, 1>{}, qa);
+                else fr[P % RING] = frag_c(std::integral_constant<int, Q>{}, std::integral_constant<int, 0>{}, smem + sb * 2 * TILE);
+            }
+        };
+        const int thr = kj - (t * BQT + 32 * HALF_B) - 4 * (lane >> 5);
+        if constexpr (!PRE) static_for<0, DIST>([&](auto p_) { request(p_); });
+        if constexpr (HB && !PRE) stat_read(std::integral_constant<int, 0>{}, sb, HALF_B);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, 16>([&](auto s_) {
+            constexpr int SL = decltype(s_)::value, e = SL;
+            float pe = 0.f, dd = 0.f;
+            // ---- vector ALU, first part: the exponential of result element SL of the current half tile
+            if constexpr (HB) {
+                if constexpr ((e & 3) == 0 && e + 4 < 16) stat_read(std::integral_constant<int, e / 4 + 1>{}, sb, HALF_B);
+                pe = fast_exp2(fmaf(sS[HALF_B][e], scale2, ckj) - l4[(e >> 2) & 1][e & 3]);
+                dd = sP[HALF_B][e] - d4[(e >> 2) & 1][e & 3];
+            }
+            auto mfma_at = [&](auto p_) __attribute__((always_inline)) {
+                constexpr int P = decltype(p_)::value;
+                if constexpr (P < NM) {
+                    constexpr int J = idx(P);
+                    if constexpr (is_a(P)) {
+                        constexpr int ks = J >> 1;
+                        if constexpr (J & 1) {
+                            if constexpr (ks == 0) mfma_v_first(sP[HALF_A], fr[P % RING], vf[0]);
+                            else mfma_v(sP[HALF_A], fr[P % RING], vf[ks]);
+                        } else {
+                            if constexpr (ks == 0) mfma_v_first(sS[HALF_A], fr[P % RING], kf[0]);
+                            else mfma_v(sS[HALF_A], fr[P % RING], kf[ks]);
+                        }
+                    } else {
+                        constexpr int kkl = J / (2 * DB), typ = (J / DB) & 1, i = J % DB;
+                        if constexpr (typ) mfma_a(dk[i], fr[P % RING], pkS[HALF_C][kkl]);
+                        else mfma_a(dv[i], fr[P % RING], pkP[HALF_C][kkl]);
                     }
+                    request(std::integral_constant<int, P + DIST>{});
+                }
+            };
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (PPS == 2) {
+                mfma_at(std::integral_constant<int, 2 * SL>{});
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // ---- vector ALU, second part: mask, dS, bf16 packing; one copy instruction; next step's statistics
+            if constexpr (HB) {
+                if constexpr (MASK) {
+                    if (erow(e) < thr) pe = 0.f;
+                }
+                const float ds = pe * dd;
+                if constexpr (e & 1) {
+                    pkP[HALF_B][e >> 3][(e & 7) - 1] = (bf16)hold_p;
+                    pkP[HALF_B][e >> 3][e & 7] = (bf16)pe;
+                    pkS[HALF_B][e >> 3][(e & 7) - 1] = (bf16)hold_s;
+                    pkS[HALF_B][e >> 3][e & 7] = (bf16)ds;
+                } else {
+                    hold_p = pe;
+                    hold_s = ds;
+                }
+                if constexpr (ODD && SL >= 1 && SL <= NCP + 1)
+                    copy_one(std::integral_constant<int, SL - 1>{}, t + 3, (t + 3 - t0) & (NST - 1));
+                if constexpr (NXT && SL == 12) {
+                    if constexpr (ODD) stat_read(std::integral_constant<int, 4>{}, (t + 1 - t0) & (NST - 1), 0);
+                    else stat_read(std::integral_constant<int, 4>{}, sb, 1);
                 }
             }
-        };
-        // steps 0..3: dV += dO^T P (fragments of gt), steps 4..7: dK += Q^T dS (fragments of qt);
-        // three fragment sets in flight, the first two requested before the element-wise phase.
-        // The accumulators live in the accumulation registers for the whole kernel and these MFMAs
-        // are issued from inline assembly ("+a"), so that the register allocator cannot shuttle
-        // them between the two register files inside the loop; the last MFMA must retire
-        // (mfma_drain) before they are read.  This relies on the accumulators never being copied
-        // inside the loop (a copy placed right after such an MFMA would read a result that is not
-        // there yet, and the compiler cannot know); the parity tests at both head sizes guard that.
-        bf16x8 cf[3][DB];
-        auto request = [&](auto st_) {
-            constexpr int st = decltype(st_)::value;
-            const bf16 *src = st < 4 ? gt : qt;
-#pragma unroll
-            for (int i = 0; i < DB; ++i) cf[st % 3][i] = T::template frag_cols<(st & 3) * 16>(src, i * 32, lane);
-        };
-        request(std::integral_constant<int, 0>{});
-        request(std::integral_constant<int, 1>{});
-        if (diag) softmax_grad(std::true_type{});
-        else softmax_grad(std::false_type{});
-        static_for<0, 8>([&](auto st_) {
-            constexpr int st = decltype(st_)::value, kk = st & 3;
-            if constexpr (st + 2 < 8) request(std::integral_constant<int, st + 2>{});
-            const bf16x8 bb = pack8(sp[(st < 4 ? 0 : 2) + (kk >> 1)], 8 * (kk & 1));
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < DB; ++i) {
-                if constexpr (st < 4) mfma_agpr(dv[i], cf[st % 3][i], bb);
-                else mfma_agpr(dk[i], cf[st % 3][i], bb);
-            }
+            mfma_at(std::integral_constant<int, PPS * SL + PPS - 1>{});
             __builtin_amdgcn_sched_barrier(0);
         });
+    };
+    using Tt = std::true_type;
+    using Ff = std::false_type;
+
+    copy_tile(t0, 0);
+    copy_tile(t0 + 1, 1);
+    copy_tile(t0 + 2, 2);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (NCP + 1)));  // tile t0 has landed, two tiles may be in flight
+    __syncthreads();
+    // prologue: A alone for half 0 of tile t0 (as the A part of an odd step of tile t0 - 1)
+    step(Tt{}, Tt{}, Ff{}, Ff{}, Ff{}, Tt{}, Ff{}, t0 - 1);
+    mfma_drain();  // the first step reads these results at once
+    stat_read(std::integral_constant<int, 0>{}, 0, 0);
+    // first tile: no half tile before it to accumulate.  Tiles t0 and t0 + 1 hold queries that precede some of
+    // the block's keys (masked form); the others do not.
+    step(Ff{}, Tt{}, Tt{}, Ff{}, Tt{}, Tt{}, Tt{}, t0);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NCP + 1));  // tile t0 + 1 has landed; tile t0 + 2 may be in flight
+    __syncthreads();
+    step(Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, t0);
+    if (t0 + 1 < t1) {
+        step(Ff{}, Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, t0 + 1);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(NCP + 1));
+        __syncthreads();
+        step(Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, t0 + 1);
     }
+    for (int t = t0 + 2; t < t1; ++t) {
+        step(Ff{}, Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, Ff{}, t);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(NCP + 1));  // tile t + 1 has landed; tile t + 2 may be in flight
+        __syncthreads();
+        step(Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, Tt{}, Ff{}, t);
+    }
+    // epilogue: C alone for half 1 of the last tile
+    step(Ff{}, Ff{}, Ff{}, Tt{}, Ff{}, Ff{}, Ff{}, t1);
     __builtin_amdgcn_s_waitcnt(0x0f70);
     mfma_drain();
 
-    if (kj < S) {
-        bf16 *kp = dqkv + ((int64_t)b * S + kj) * ld + d + hd * DH + 4 * (lane >> 5);
+    // Results leave through LDS: a lane holds 4 consecutive dh of one key per register group, the rows of dK and dV
+    // are DH contiguous elements in memory.  Each wave stages its 32 keys x DH block (16-byte chunks XOR-swizzled by
+    // the key) and writes whole rows, 16 bytes per lane.
+    __syncthreads();  // every wave has finished reading the last tile
+    {
+        constexpr int NCH = DH / 8;        // 16-byte chunks per row
+        constexpr int RPI = 64 / NCH;      // rows per store instruction
+        bf16 *buf = smem + wave * (2 * 32 * DH);
+        const int key = lane & 31, hh = lane >> 5;
 #pragma unroll
         for (int i = 0; i < DB; ++i)
 #pragma unroll
@@ -646,9 +773,22 @@ __global__ __launch_bounds__(256, 1) void flash_bwd_dkv_kernel(const bf16 *__res
                     a[x] = (bf16)(dk[i][4 * e4 + x] * scale);
                     c[x] = (bf16)dv[i][4 * e4 + x];
                 }
-                *reinterpret_cast<bf16x4 *>(kp + i * 32 + 8 * e4) = a;
-                *reinterpret_cast<bf16x4 *>(kp + d + i * 32 + 8 * e4) = c;
+                const int ch = ((4 * i + e4) ^ (key & (NCH - 1))) * 8 + 4 * hh;
+                *reinterpret_cast<bf16x4 *>(buf + key * DH + ch) = a;
+                *reinterpret_cast<bf16x4 *>(buf + 32 * DH + key * DH + ch) = c;
             }
+        bf16 *gp = dqkv + ((int64_t)b * S + jw) * ld + d + hd * DH;
+#pragma unroll
+        for (int j = 0; j < 32 / RPI; ++j) {
+            const int r = j * RPI + lane / NCH, cc = lane % NCH;
+            const int at = r * DH + ((cc ^ (r & (NCH - 1))) * 8);
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(buf + at);
+            const bf16x8 c = *reinterpret_cast<const bf16x8 *>(buf + 32 * DH + at);
+            if (jw + r < S) {
+                *reinterpret_cast<bf16x8 *>(gp + (int64_t)r * ld + cc * 8) = a;
+                *reinterpret_cast<bf16x8 *>(gp + (int64_t)r * ld + d + cc * 8) = c;
+            }
+        }
     }
 }
 
