@@ -531,7 +531,6 @@ __global__ __launch_bounds__(256, 1) void flash_bwd_dkv_kernel(const bf16 *__res
     const int d = H * DH, ld = 3 * d;
     const int jb = (blockIdx.x / (gridDim.x / nkb)) * BKB, jw = jb + wave * 32;
     const int kj = jw + (lane & 31);
-    const int kr = kj < S ? kj : S - 1;
     const bf16 *base = qkv + (int64_t)b * S * ld;
     const bf16 *gbase = d_o + (int64_t)b * S * d;
     const rsrc_t rq = make_rsrc(base, (uint32_t)((int64_t)S * ld * 2));
@@ -546,15 +545,6 @@ __global__ __launch_bounds__(256, 1) void flash_bwd_dkv_kernel(const bf16 *__res
     // K^T and V^T operands (lane = key, 8 consecutive dh per k-step) live in the accumulation registers for the
     // whole kernel: loaded there directly, read from there by the MFMAs
     bf16x8 kf[KS], vf[KS];
-    {
-        const bf16 *kp = base + (int64_t)kr * ld + d + hd * DH + 8 * (lane >> 5);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(kf[ks]) : "v"(kp + 16 * ks) : "memory");
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(vf[ks]) : "v"(kp + d + 16 * ks) : "memory");
-        }
-        // (no wait here: loads retire in order, so the wait for the first tile's copies below covers these)
-    }
     f32x16 dk[DB], dv[DB];
 #pragma unroll
     for (int i = 0; i < DB; ++i) {
@@ -722,11 +712,39 @@ __global__ __launch_bounds__(256, 1) void flash_bwd_dkv_kernel(const bf16 *__res
     using Tt = std::true_type;
     using Ff = std::false_type;
 
+    // The block's K and V rows come through LDS as well (whole rows, coalesced; a load straight into the operand
+    // layout would touch 64 different rows per instruction): K into stage 2, V into stage 3, which the query tiles
+    // do not need yet, then one 16-byte LDS read per k-step into the accumulation registers.
+    {
+        constexpr int NKV = BKB / T::ROWS_PER_INST / 4;  // copy instructions per wave and matrix
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int c = 0; c < NKV; ++c) {
+                const int inst = wave * NKV + c;
+                const int r = inst * T::ROWS_PER_INST + lane / T::NC;
+                const int cc = (lane % T::NC) ^ T::swz(r);
+                const int vo = jb + r < S ? (lane / T::NC) * ld * 2 + cc * 16 : 0x7fffffff;  // rows past the end: not read
+                copy16_to_lds(rq, lds_addr(smem + (2 + m) * 2 * TILE) + inst * 1024, vo,
+                              (jb + inst * T::ROWS_PER_INST) * ld * 2 + ((1 + m) * d + hd * DH) * 2);
+            }
+    }
     copy_tile(t0, 0);
     copy_tile(t0 + 1, 1);
-    copy_tile(t0 + 2, 2);
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * (NCP + 1)));  // tile t0 has landed, two tiles may be in flight
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NCP + 1));  // K, V and tile t0 have landed, tile t0 + 1 may be in flight
     __syncthreads();
+    {
+        const int r = wave * 32 + (lane & 31);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const unsigned at = lds_addr(smem + 2 * 2 * TILE + r * DH + (((2 * ks + (lane >> 5)) ^ T::swz(r)) << 3));
+            asm volatile("ds_read_b128 %0, %1" : "=a"(kf[ks]) : "v"(at) : "memory");
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=a"(vf[ks]) : "v"(at), "i"(2 * TILE * 2) : "memory");
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
+    __syncthreads();  // stages 2 and 3 are free again
+    copy_tile(t0 + 2, 2);
     // prologue: A alone for half 0 of tile t0 (as the A part of an odd step of tile t0 - 1)
     step(Tt{}, Tt{}, Ff{}, Ff{}, Ff{}, Tt{}, Ff{}, t0 - 1);
     mfma_drain();  // the first step reads these results at once
