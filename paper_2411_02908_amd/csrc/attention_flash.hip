@@ -328,38 +328,12 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const bf16 *__restric
 // tiles for a block of queries (dQ), the other walks the query tiles for a block of keys
 // (dK, dV).
 
-// dvec[b, h, i] = sum_c dO[i, h, c] * O[i, h, c], and lseb[b, h, i] = lse[b, h, i] + slope_h * i (log2
-// units): the query-dependent part of the exponent p_ij = 2^(s_ij - lseb_i + slope_h * j), so that the
-// dK / dV kernel spends one subtraction per score on it.
-template <int DH>
-__global__ __launch_bounds__(256) void flash_bwd_dot_kernel(const bf16 *__restrict__ o, const bf16 *__restrict__ d_o,
-                                                             const float *__restrict__ lse, float *__restrict__ dvec,
-                                                             float *__restrict__ lseb, int H, int S) {
-    constexpr int G = DH / 8;  // lanes per head
-    const int m = blockIdx.x;  // row b * S + i
-    const int d = H * DH;
-    for (int c = threadIdx.x; c < d / 8; c += 256) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(o + (int64_t)m * d + c * 8);
-        const bf16x8 g = *reinterpret_cast<const bf16x8 *>(d_o + (int64_t)m * d + c * 8);
-        float s = 0.f;
-#pragma unroll
-        for (int x = 0; x < 8; ++x) s = fmaf((float)a[x], (float)g[x], s);
-#pragma unroll
-        for (int off = G / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-        if ((c % G) == 0) {
-            const int hd = c / G;
-            const int64_t at = ((int64_t)(m / S) * H + hd) * S + (m % S);
-            dvec[at] = s;
-            lseb[at] = lse[at] + exp2f(-8.0f * (float)(hd + 1) / (float)H) * kLog2e * (float)(m % S);
-        }
-    }
-}
-
 template <int DH>
 __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const bf16 *__restrict__ qkv,
+                                                               const bf16 *__restrict__ o,
                                                                const bf16 *__restrict__ d_o,
                                                                const float *__restrict__ lse,
-                                                               const float *__restrict__ dvec,
+                                                               float *__restrict__ dvec, float *__restrict__ lseb,
                                                                bf16 *__restrict__ dqkv, int H, int S) {
     using T = Tile<DH>;
     constexpr int KS = DH / 16, DB = DH / 32;
@@ -380,18 +354,34 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const bf16 *__rest
     const float slope2 = exp2f(-8.0f * (float)(hd + 1) / (float)H) * kLog2e;
     const float scale = rsqrtf((float)DH), scale2 = scale * kLog2e;
 
+    // Q^T and dO^T operands (lane = query, 8 consecutive dh per k-step); D_i = dO_i . O_i falls out of the same
+    // rows: each lane sums its half of the row, the two halves meet through one exchange.  This kernel owns its
+    // queries, so it also writes D_i and lse_i + slope i (log2 units: the query-dependent part of the exponent
+    // p_ij = 2^(s_ij - lse_i - slope i + slope j)) for the dK / dV kernel, which runs after it.
     bf16x8 qf[KS], dof[KS];
+    float Di = 0.f;
     {
         const bf16 *qp = base + (int64_t)qr * ld + hd * DH + 8 * (lane >> 5);
         const bf16 *gp = d_o + ((int64_t)b * S + qr) * d + hd * DH + 8 * (lane >> 5);
+        const bf16 *op = o + ((int64_t)b * S + qr) * d + hd * DH + 8 * (lane >> 5);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
             dof[ks] = *reinterpret_cast<const bf16x8 *>(gp + 16 * ks);
         }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 of = *reinterpret_cast<const bf16x8 *>(op + 16 * ks);
+#pragma unroll
+            for (int x = 0; x < 8; ++x) Di = fmaf((float)dof[ks][x], (float)of[x], Di);
+        }
+        Di += __shfl_xor(Di, 32, 64);
     }
     const float lse2 = lse[((int64_t)b * H + hd) * S + qr];  // saved in log2 units
-    const float Di = dvec[((int64_t)b * H + hd) * S + qr];
+    if (lane < 32 && qi < S) {
+        dvec[((int64_t)b * H + hd) * S + qi] = Di;
+        lseb[((int64_t)b * H + hd) * S + qi] = lse2 + slope2 * (float)qi;
+    }
     // Bias of result element e relative to the 32-key block: slope (crow(e) - query) - lse, with
     // crow(e) = 8 (e / 4) + 4 (lane / 32) + e % 4.  The e % 4 part lives in four per-lane constants,
     // the 8 (e / 4) part joins the per-block offset below (same instruction count, 12 registers less).
@@ -830,12 +820,10 @@ bool attention_bwd_flash_bf16(hipStream_t st, const bf16 *qkv, const bf16 *o, co
     const dim3 gq(((S + FQ - 1) / FQ) * H * B), gk(((S + BKB - 1) / BKB) * H * B), block(256);
     float *lseb = dvec + (int64_t)B * H * S;  // second half of the scratch
     if (Dh == 128) {
-        hipLaunchKernelGGL((flash_bwd_dot_kernel<128>), dim3(B * S), block, 0, st, o, d_o, lse, dvec, lseb, H, S);
-        hipLaunchKernelGGL((flash_bwd_dq_kernel<128>), gq, block, 0, st, qkv, d_o, lse, dvec, dqkv, H, S);
+        hipLaunchKernelGGL((flash_bwd_dq_kernel<128>), gq, block, 0, st, qkv, o, d_o, lse, dvec, lseb, dqkv, H, S);
         hipLaunchKernelGGL((flash_bwd_dkv_kernel<128>), gk, block, 0, st, qkv, d_o, lseb, dvec, dqkv, H, S);
     } else {
-        hipLaunchKernelGGL((flash_bwd_dot_kernel<64>), dim3(B * S), block, 0, st, o, d_o, lse, dvec, lseb, H, S);
-        hipLaunchKernelGGL((flash_bwd_dq_kernel<64>), gq, block, 0, st, qkv, d_o, lse, dvec, dqkv, H, S);
+        hipLaunchKernelGGL((flash_bwd_dq_kernel<64>), gq, block, 0, st, qkv, o, d_o, lse, dvec, lseb, dqkv, H, S);
         hipLaunchKernelGGL((flash_bwd_dkv_kernel<64>), gk, block, 0, st, qkv, d_o, lseb, dvec, dqkv, H, S);
     }
     return true;

@@ -100,12 +100,15 @@ __global__ __launch_bounds__(256) void embedding_gather_kernel(const float *__re
     for (int c = threadIdx.x; c < d / 4; c += 256) dst[c] = src[c];
 }
 
-// One workgroup per input position m.  The first position holding a token id owns that id's
-// row of dE: it collects the later positions with the same id, in increasing order, into an
-// LDS list (ordered compaction, 256 positions at a time) and then adds their rows in that
-// order -- a fixed summation order without atomics, and the frequent ids of a Zipf stream do
-// not serialise on a chain of dependent token loads.
+// One workgroup per input position m and slice of 1024 columns.  The first position holding a
+// token id owns that id's row of dE: it collects the later positions with the same id, in
+// increasing order, into an LDS list (ordered compaction, 256 positions at a time) and then adds
+// their rows in that order -- a fixed summation order without atomics.  The frequent ids of a
+// Zipf stream make chains of hundreds of rows that one workgroup walks alone: sixteen row loads
+// are in flight per thread and the columns are split over workgroups, so that such a chain is
+// bound by bandwidth, not by one memory latency per row.
 constexpr int SCATTER_LIST = 4096;
+constexpr int SCATTER_COLS = 1024;
 __global__ __launch_bounds__(256) void embedding_scatter_kernel(const float *__restrict__ dx0,
                                                                  const int32_t *__restrict__ tokens,
                                                                  float *__restrict__ dE, int S, int M, int d) {
@@ -113,29 +116,33 @@ __global__ __launch_bounds__(256) void embedding_scatter_kernel(const float *__r
     __shared__ int list[SCATTER_LIST];
     __shared__ int wave_cnt[4];
     const int m = blockIdx.x;
-    const int tok = tokens[(m / S) * (S + 1) + (m % S)];
+    const int mb = m / S, ms = m - mb * S;
+    const int tok = tokens[mb * (S + 1) + ms];
     if (threadIdx.x == 0) earlier = 0;
     __syncthreads();
+    // does an earlier position hold the same id?  (rows of S + 1 ids, the last one a target only)
     int found = 0;
-    for (int p = threadIdx.x; p < m; p += 256) found |= (tokens[(p / S) * (S + 1) + (p % S)] == tok);
+    for (int b = 0; b <= mb; ++b) {
+        const int32_t *row = tokens + b * (S + 1);
+        const int n = b < mb ? S : ms;
+        for (int p = threadIdx.x; p < n; p += 256) found |= (row[p] == tok);
+    }
     if (found) earlier = 1;
     __syncthreads();
     if (earlier) return;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    f32x4 acc[4];  // columns 4 * (threadIdx.x + 256 * i): d <= 4096
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int c = 4 * (threadIdx.x + 256 * i);
-        acc[i] = c < d ? *reinterpret_cast<const f32x4 *>(dE + (int64_t)tok * d + c) : f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    const int c = blockIdx.y * SCATTER_COLS + 4 * threadIdx.x;  // this thread's four columns
+    const bool live = c < d;
+    f32x4 acc = live ? *reinterpret_cast<const f32x4 *>(dE + (int64_t)tok * d + c) : f32x4{0.f, 0.f, 0.f, 0.f};
     int p0 = m;
     while (p0 < M) {
         // fill the list with matching positions from p0 on, in order
         int base = 0;
         while (p0 < M && base + 256 <= SCATTER_LIST) {
             const int p = p0 + threadIdx.x;
-            const bool hit = p < M && tokens[(p / S) * (S + 1) + (p % S)] == tok;
+            const int pb = p / S;
+            const bool hit = p < M && tokens[pb * (S + 1) + (p - pb * S)] == tok;
             const unsigned long long mask = __ballot(hit);
             const int before = __popcll(mask & ((1ull << lane) - 1ull));
             if (lane == 0) wave_cnt[wave] = __popcll(mask);
@@ -147,39 +154,22 @@ __global__ __launch_bounds__(256) void embedding_scatter_kernel(const float *__r
             __syncthreads();
             p0 += 256;
         }
-        // rows are added in list order; the loads of eight rows are issued together so that the
-        // chain of a frequent id is bound by bandwidth, not by one memory latency per row
-        constexpr int UR = 8;
+        // rows are added in list order, sixteen loads in flight
+        constexpr int UR = 16;
         for (int q0 = 0; q0 < base; q0 += UR) {
-            f32x4 r[UR][4];
+            f32x4 r[UR];
 #pragma unroll
             for (int u = 0; u < UR; ++u) {
                 const int q = q0 + u < base ? q0 + u : base - 1;
-                const float *row = dx0 + (int64_t)list[q] * d;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int c = 4 * (threadIdx.x + 256 * i);
-                    if (c < d) r[u][i] = *reinterpret_cast<const f32x4 *>(row + c);
-                }
+                if (live) r[u] = *reinterpret_cast<const f32x4 *>(dx0 + (int64_t)list[q] * d + c);
             }
 #pragma unroll
-            for (int u = 0; u < UR; ++u) {
-                if (q0 + u < base) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int c = 4 * (threadIdx.x + 256 * i);
-                        if (c < d) acc[i] += r[u][i];
-                    }
-                }
-            }
+            for (int u = 0; u < UR; ++u)
+                if (live && q0 + u < base) acc += r[u];
         }
         __syncthreads();
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int c = 4 * (threadIdx.x + 256 * i);
-        if (c < d) *reinterpret_cast<f32x4 *>(dE + (int64_t)tok * d + c) = acc[i];
-    }
+    if (live) *reinterpret_cast<f32x4 *>(dE + (int64_t)tok * d + c) = acc;
 }
 
 // ------------------------------------------------------------------------------------ LayerNorm
@@ -628,6 +618,73 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(T *__restrict__ logi
     }
 }
 
+// The same with the row held in registers between the two passes (NV 16-byte vectors per thread,
+// V <= 256 * NV * VEC): the second pass of the kernel above finds its row neither in L2 nor, with
+// thousands of 100 KB rows in flight, reliably in the last-level cache, so it costs a third read.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void cross_entropy_regs_kernel(T *__restrict__ logits, int ldz, int V,
+                                                                  const int32_t *__restrict__ tokens, int S, int m0,
+                                                                  float *__restrict__ loss_rows, float scale) {
+    __shared__ float red[256 / PHOTON_WAVE];
+    constexpr int VEC = 16 / sizeof(T);
+    typedef T vec_t __attribute__((ext_vector_type(VEC)));
+    const int m = m0 + blockIdx.x;
+    T *z = logits + (int64_t)blockIdx.x * ldz;
+    const int tgt = tokens[(m / S) * (S + 1) + (m % S) + 1];
+    const int nvec = V / VEC;
+    vec_t v[NV];
+    float mx = -INFINITY;
+    // all loads first (a vector past the end re-reads vector 0 and is ignored below), so that they are in flight
+    // together
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = threadIdx.x + 256 * j;
+        v[j] = *reinterpret_cast<const vec_t *>(z + (i < nvec ? i : 0) * VEC);
+    }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = threadIdx.x + 256 * j;
+        if (i < nvec) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) mx = fmaxf(mx, to_f32(v[j][k]));
+        }
+    }
+    for (int c = nvec * VEC + threadIdx.x; c < V; c += 256) mx = fmaxf(mx, to_f32(z[c]));
+    const float gmx = block_max<256>(mx, red);
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = threadIdx.x + 256 * j;
+        if (i < nvec) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) sum += __expf(to_f32(v[j][k]) - gmx);
+        }
+    }
+    for (int c = nvec * VEC + threadIdx.x; c < V; c += 256) sum += __expf(to_f32(z[c]) - gmx);
+    const float gsum = block_sum<256>(sum, red);
+    const float lse = gmx + __logf(gsum);
+    if (threadIdx.x == 0) loss_rows[m] = lse - to_f32(z[tgt]);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int i = threadIdx.x + 256 * j;
+        if (i < nvec) {
+            vec_t o;
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                const int c = i * VEC + k;
+                o[k] = from_f32<T>((__expf(to_f32(v[j][k]) - lse) - (c == tgt ? 1.0f : 0.0f)) * scale);
+            }
+            *reinterpret_cast<vec_t *>(z + i * VEC) = o;
+        }
+    }
+    for (int c = nvec * VEC + threadIdx.x; c < ldz; c += 256) {
+        float g = 0.f;
+        if (c < V) g = (__expf(to_f32(z[c]) - lse) - (c == tgt ? 1.0f : 0.0f)) * scale;
+        z[c] = from_f32<T>(g);
+    }
+}
+
 __global__ __launch_bounds__(256) void loss_reduce_kernel(const float *__restrict__ rows, int M, double scale,
                                                            double *__restrict__ acc) {
     __shared__ double s[256];
@@ -754,7 +811,8 @@ void embedding_gather(hipStream_t st, const float *E, const int32_t *tokens, flo
 }
 
 void embedding_scatter_add(hipStream_t st, const float *dx0, const int32_t *tokens, float *dE, int B, int S, int d) {
-    hipLaunchKernelGGL(embedding_scatter_kernel, dim3(B * S), dim3(256), 0, st, dx0, tokens, dE, S, B * S, d);
+    hipLaunchKernelGGL(embedding_scatter_kernel, dim3(B * S, (d + SCATTER_COLS - 1) / SCATTER_COLS), dim3(256), 0, st, dx0,
+                       tokens, dE, S, B * S, d);
 }
 
 template <typename T>
@@ -862,8 +920,13 @@ void attention_bwd<bf16>(hipStream_t st, const bf16 *qkv, const bf16 *o, const f
 template <typename T>
 void cross_entropy_fwd_bwd(hipStream_t st, T *logits, int ldz, int V, const int32_t *tokens, int S, int m0, int rows,
                            float *loss_rows, float scale) {
-    hipLaunchKernelGGL((cross_entropy_kernel<T>), dim3(rows), dim3(256), 0, st, logits, ldz, V, tokens, S, m0, loss_rows,
-                       scale);
+    constexpr int VEC = 16 / sizeof(T), NV = 26;  // rows of up to 256 * 26 * VEC ids stay in registers
+    if (V / VEC <= 256 * NV && sizeof(T) == 2)
+        hipLaunchKernelGGL((cross_entropy_regs_kernel<T, NV>), dim3(rows), dim3(256), 0, st, logits, ldz, V, tokens, S, m0,
+                           loss_rows, scale);
+    else
+        hipLaunchKernelGGL((cross_entropy_kernel<T>), dim3(rows), dim3(256), 0, st, logits, ldz, V, tokens, S, m0,
+                           loss_rows, scale);
 }
 template void cross_entropy_fwd_bwd<float>(hipStream_t, float *, int, int, const int32_t *, int, int, int, float *, float);
 template void cross_entropy_fwd_bwd<bf16>(hipStream_t, bf16 *, int, int, const int32_t *, int, int, int, float *, float);
