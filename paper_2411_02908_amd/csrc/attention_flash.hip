@@ -478,15 +478,20 @@ constexpr int BQT = 64;   // queries per tile (two halves of 32)
 // s_waitcnt immediate: vmcnt = n (low four bits and bits 15:14), the other counters left alone
 constexpr int vmcnt_imm(int n) { return 0x0f70 | (n & 15) | ((n >> 4) << 14); }
 
-// acc (+)= a * b, accumulator in the accumulation registers
+// MFMAs of the pipelined loop, issued from inline assembly so that operands and accumulators stay in the register
+// file this kernel assigns them (K / V operands and dK / dV in the accumulation registers, S / dP in architectural
+// ones).  The compiler cannot see their hazards; none needs a wait state here: every operand written by the vector
+// ALU (the bf16 packs) is a whole step old, fragments come from LDS behind a wait count, a chain's next MFMA on the
+// same accumulator is at least two MFMAs away, and results are read by the vector ALU two slots (four MFMAs) or more
+// after the chain's last MFMA issued (mfma_drain() where that does not hold).
 __device__ __forceinline__ void mfma_v(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
 }
 __device__ __forceinline__ void mfma_v_first(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
 }
 __device__ __forceinline__ void mfma_a(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
 // dK / dV for a block of 128 keys, walking the query tiles at or after it.  One wave per SIMD, so
@@ -521,6 +526,7 @@ __global__ __launch_bounds__(256, 1) void flash_bwd_dkv_kernel(const bf16 *__res
     const int d = H * DH, ld = 3 * d;
     const int jb = (blockIdx.x / (gridDim.x / nkb)) * BKB, jw = jb + wave * 32;
     const int kj = jw + (lane & 31);
+    const int kr = kj < S ? kj : S - 1;
     const bf16 *base = qkv + (int64_t)b * S * ld;
     const bf16 *gbase = d_o + (int64_t)b * S * d;
     const rsrc_t rq = make_rsrc(base, (uint32_t)((int64_t)S * ld * 2));
