@@ -144,6 +144,10 @@ BF16_SHAPES = [
     # every GEMM depth an odd multiple of 32 (d = 5 x 32, d_ff = 19 x 32, 2 x 112 = 7 x 32 tokens):
     # the K loop's tail step and half-filled last staged tile; odd vocabulary, Dh = 32
     ModelShape(1, 160, 5, 608, 777, 112),
+    # flash attention kernels with several key blocks and a half-filled last one (S = 2.5 and 1.5 blocks of 128 keys:
+    # keys past the end of the sequence, a last block with a single query tile), at both head sizes
+    ModelShape(1, 256, 2, 512, 300, 320),     # Dh = 128
+    ModelShape(1, 128, 2, 256, 300, 192),     # Dh = 64
 ]
 
 
