@@ -13,7 +13,8 @@
 //
 // K / V (and Q / dO in the backward kernels) tiles are copied global -> LDS directly by
 // buffer_load_dwordx4 ... lds (issued from inline assembly, see copy16_to_lds), XOR-swizzled in
-// 16-byte chunks, double-buffered.
+// 16-byte chunks, double-buffered (four stages in the dK / dV kernel).  Results whose register
+// layout would give 8-byte pieces of 32 rows per store (dK, dV) leave through LDS as whole rows.
 
 #include "kernels.h"
 
@@ -542,11 +543,6 @@ __global__ __launch_bounds__(256, 1) void flash_bwd_dkv_kernel(const bf16 *__res
     // whole kernel: loaded there directly, read from there by the MFMAs
     bf16x8 kf[KS], vf[KS];
     f32x16 dk[DB], dv[DB];
-#pragma unroll
-    for (int i = 0; i < DB; ++i) {
-        mfma_agpr_zero(dk[i]);
-        mfma_agpr_zero(dv[i]);
-    }
     const float ckj = slope2 * (float)kj;
 
     const int t0 = jb / BQT, t1 = S / BQT;
@@ -727,6 +723,12 @@ __global__ __launch_bounds__(256, 1) void flash_bwd_dkv_kernel(const bf16 *__res
     }
     copy_tile(t0, 0);
     copy_tile(t0 + 1, 1);
+    // (the accumulators are cleared while the copies are in flight)
+#pragma unroll
+    for (int i = 0; i < DB; ++i) {
+        mfma_agpr_zero(dk[i]);
+        mfma_agpr_zero(dv[i]);
+    }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(NCP + 1));  // K, V and tile t0 have landed, tile t0 + 1 may be in flight
     __syncthreads();
     {
